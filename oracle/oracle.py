@@ -1,0 +1,128 @@
+"""ctypes front end of the CPU oracle -- TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT.
+
+Only the tests, the smoke check and the benchmark's CPU-baseline leg may import this
+module.  It loads `libsolar_oracle.so`, built from `solar_oracle.c` with plain gcc,
+and converts numpy arrays to the double-precision host buffers the C code expects.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "solar_oracle.c")
+_LIB = os.path.join(_HERE, "libsolar_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, no BLAS, no threads)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True, cwd=_HERE)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        ci = ctypes.c_int
+        _lib.solar_oracle_gram.argtypes = [dp, ip, ci, ci, ci, dp]
+        _lib.solar_oracle_svd_factorize.argtypes = [dp, ip, ci, ci, ci, ci, dp, dp, dp, dp, ip]
+        _lib.solar_oracle_svd_attention.argtypes = [dp, dp, ip, dp, dp, ci, ci, ci, ci, ci,
+                                                    ctypes.c_double, ci, dp]
+        _lib.solar_oracle_dense_attention.argtypes = [dp, dp, ip, ci, ci, ci, ci,
+                                                      ctypes.c_double, dp]
+        for f in (_lib.solar_oracle_gram, _lib.solar_oracle_svd_factorize,
+                  _lib.solar_oracle_svd_attention, _lib.solar_oracle_dense_attention):
+            f.restype = ci
+    return _lib
+
+
+def _d(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _i(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _len(lengths) -> Optional[np.ndarray]:
+    return None if lengths is None else np.ascontiguousarray(lengths, dtype=np.int32)
+
+
+def gram(X, lengths=None) -> np.ndarray:
+    X = _f64(X)
+    B, N, d = X.shape
+    L = _len(lengths)
+    G = np.empty((B, d, d), dtype=np.float64)
+    rc = _load().solar_oracle_gram(_d(X), _i(L), B, N, d, _d(G))
+    if rc != 0:
+        raise RuntimeError(f"solar_oracle_gram failed: {rc}")
+    return G
+
+
+def svd_factorize(X, r: int, lengths=None, want_u: bool = False, want_full: bool = False):
+    """Returns dict(S [B,r], V [B,d,r], U [B,N,r] or None, S_full [B,d] or None, info [B])."""
+    X = _f64(X)
+    B, N, d = X.shape
+    L = _len(lengths)
+    S = np.empty((B, r), dtype=np.float64)
+    V = np.empty((B, d, r), dtype=np.float64)
+    U = np.zeros((B, N, r), dtype=np.float64) if want_u else None
+    SF = np.zeros((B, d), dtype=np.float64) if want_full else None
+    info = np.zeros((B,), dtype=np.int32)
+    rc = _load().solar_oracle_svd_factorize(_d(X), _i(L), B, N, d, r, _d(S), _d(V), _d(U),
+                                            _d(SF), _i(info))
+    if rc < 0:
+        raise RuntimeError(f"solar_oracle_svd_factorize failed: {rc}")
+    return dict(S=S, V=V, U=U, S_full=SF, info=info, status=rc)
+
+
+def svd_attention(Q, X, S, V, scale: float, mode: int, lengths=None) -> np.ndarray:
+    Q = _f64(Q)
+    S = _f64(S)
+    V = _f64(V)
+    B, M, d = Q.shape
+    r = S.shape[1]
+    if X is not None:
+        X = _f64(X)
+        N = X.shape[1]
+    else:
+        N = 1
+    L = _len(lengths)
+    O = np.empty((B, M, d), dtype=np.float64)
+    rc = _load().solar_oracle_svd_attention(_d(Q), _d(X), _i(L), _d(S), _d(V), B, N, d, r, M,
+                                            float(scale), int(mode), _d(O))
+    if rc != 0:
+        raise RuntimeError(f"solar_oracle_svd_attention failed: {rc}")
+    return O
+
+
+def dense_attention(Q, X, scale: float, lengths=None) -> np.ndarray:
+    Q = _f64(Q)
+    X = _f64(X)
+    B, M, d = Q.shape
+    N = X.shape[1]
+    L = _len(lengths)
+    O = np.empty((B, M, d), dtype=np.float64)
+    rc = _load().solar_oracle_dense_attention(_d(Q), _d(X), _i(L), B, N, d, M, float(scale), _d(O))
+    if rc != 0:
+        raise RuntimeError(f"solar_oracle_dense_attention failed: {rc}")
+    return O
