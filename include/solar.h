@@ -1,0 +1,142 @@
+/*
+ * solar.h -- C ABI of the MI355X (gfx950) SVD-Attention library.
+ *
+ * SVD-Attention (Section "SVD-Attention" of the SOLAR paper): each user's N x d
+ * behaviour-sequence matrix X is given a rank-r truncated SVD, X = U S V^T, and M
+ * candidate items attend to the sequence through the factors, so that the cost is
+ * O(N d r) instead of the O(N^2 d) of dense softmax attention.
+ *
+ * Conventions shared by every entry point
+ *   - Every array pointer is a DEVICE pointer owned by the caller (for example a
+ *     torch tensor's data_ptr()).  The library never allocates or frees device
+ *     memory and never synchronizes: all work is enqueued on `stream`, a
+ *     hipStream_t passed as void* (NULL = the default stream).
+ *   - Arrays are row-major with the last index contiguous.  B users, N rows per
+ *     (padded) sequence, d embedding columns, r rank, M candidates.
+ *   - `lengths` ([B] int32, device) holds the number of valid rows of each user;
+ *     NULL means every user has N valid rows.  Rows at or past the valid length
+ *     are never read as data: they are left out of the factorization and masked
+ *     out of every softmax, whatever they contain.
+ *   - X and Q have element type `t` (float or bf16 bit patterns); every output
+ *     is float.
+ *   - Supported shapes: d in {64, 128, 256}; 1 <= r <= min(d, 64) (r <= 32 when
+ *     d = 256); N, M, B >= 1.  Anything else returns SOLAR_ERR_UNSUPPORTED.
+ *   - Errors: a status code is returned, nothing is printed and nothing aborts.
+ *     Arguments are validated on the host before any launch; on an argument
+ *     error no kernel runs and the outputs are untouched.  Conditions that only
+ *     the device can see (a bad entry of `lengths`, an eigen-iteration that did
+ *     not converge) are reported per user through `info`.
+ *   - `workspace` is caller-owned device scratch of at least
+ *     solar_workspace_bytes(...) bytes, 256-byte aligned.  Its contents are
+ *     undefined on return.  Two calls that share a workspace must be ordered on
+ *     one stream.
+ */
+#ifndef SOLAR_H
+#define SOLAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SOLAR_OK = 0,
+    SOLAR_ERR_INVALID_ARG = 1,
+    SOLAR_ERR_UNSUPPORTED = 2,
+    SOLAR_ERR_WORKSPACE = 3,
+    SOLAR_ERR_HIP = 4
+} solar_status;
+
+typedef enum { SOLAR_F32 = 0, SOLAR_BF16 = 1 } solar_dtype;
+
+/* Where the softmax of Attn_SVD sits (the paper's formula omits it; see the
+ * operator definitions in Section "SVD-Attention" and the "without Softmax" row
+ * of the attention-ablation table). */
+typedef enum {
+    SOLAR_ATTN_SEQ_SOFTMAX = 0,   /* softmax over the N sequence positions, evaluated in
+                                     factor space; equals dense softmax attention when
+                                     rank(X) <= r                                          */
+    SOLAR_ATTN_EIGEN_SOFTMAX = 1, /* literal form: softmax over the r rows of (V S)^T       */
+    SOLAR_ATTN_LINEAR = 2         /* the same without softmax: scale * Q (V S^2 V^T)        */
+} solar_attn_mode;
+
+/* Human-readable name of a status code (static string, host memory). */
+const char* solar_status_string(solar_status s);
+
+/* Bytes of device scratch that any of the calls below needs for these sizes. */
+size_t solar_workspace_bytes(int B, int N, int d, int r, int M, solar_dtype t);
+
+/*
+ * Factorization step: rank-r truncated SVD of every user's valid rows
+ * (truncated-SVD equation of Section "SVD-Attention"; Algorithm 1, "Randomized
+ * SVD with Power Iteration", whose outputs s and R are S and V here).
+ *
+ * The power iteration Omega <- X^T (X Omega) of Algorithm 1 is applied through
+ * the Gram matrix G = X^T X, formed in one pass over X; the subspace iteration
+ * and the small decomposition then run on G, one workgroup per user.  U is never
+ * formed ("we eliminate U"); instead the projection P = X V (= U S) is returned.
+ *
+ *   X        in  [B,N,d] of type t
+ *   lengths  in  [B] or NULL
+ *   S        out [B,r]   singular values, descending
+ *   V        out [B,d,r] right singular vectors; each column's largest-magnitude
+ *                        entry is positive.  Components whose singular value is
+ *                        below about 3e-3 of the largest cannot be resolved
+ *                        through a float Gram matrix: they come back as S = 0 with
+ *                        a zero column of V.
+ *   P        out [B,N,r] = X V, rows at or past the valid length are zero; may be
+ *                        NULL if only modes 1 and 2 will be used
+ *   info     out [B] or NULL: 0 converged; k > 0 iteration cap reached after k
+ *                        steps (results are the best available); -1 bad length
+ *                        (not in [r, N]; that user's outputs are zero)
+ */
+solar_status solar_svd_factorize(const void* X, const int32_t* lengths, int B, int N, int d,
+                                 int r, solar_dtype t, float* S, float* V, float* P,
+                                 int32_t* info, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
+/*
+ * Attention step, Attn_SVD = MatMul(MatMul(Query, Key_r^T), Value_r) with
+ * W_Q = W_K = W_V = I (fold W_Q W_K^T into Q before the call and apply W_V to O
+ * after it).
+ *
+ *   mode 0:  O = softmax_n(scale * (Q V) P^T) P V^T      (needs P, lengths)
+ *   mode 1:  O = softmax_k(scale * Q T^T) T,  T = diag(S) V^T   (r <= 64)
+ *   mode 2:  O = scale * (Q T^T) T
+ *
+ *   Q        in  [B,M,d] of type t
+ *   S, V, P  in  as written by solar_svd_factorize (P may be NULL for modes 1, 2)
+ *   O        out [B,M,d]
+ */
+solar_status solar_svd_attention(const void* Q, const float* S, const float* V, const float* P,
+                                 const int32_t* lengths, int B, int N, int d, int r, int M,
+                                 float scale, solar_attn_mode mode, solar_dtype t, float* O,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Dense softmax attention over the raw sequence (Preliminaries, Attn_sm with
+ * Key = Value = X): O = softmax_n(scale * Q X^T) X over the valid rows.  A
+ * straightforward float kernel kept as the on-device reference for what
+ * SVD-Attention replaces; it is not tuned.
+ */
+solar_status solar_dense_attention_ref(const void* Q, const void* X, const int32_t* lengths,
+                                       int B, int N, int d, int M, float scale, solar_dtype t,
+                                       float* O, void* workspace, size_t workspace_bytes,
+                                       void* stream);
+
+/*
+ * First phase of the factorization on its own, exported so that it can be checked
+ * and profiled in isolation: G_b = X_b^T X_b over the valid rows, the contraction
+ * over the sequence axis that Algorithm 1's power iteration applies to Omega.
+ *   G        out [B,d,d]
+ */
+solar_status solar_gram(const void* X, const int32_t* lengths, int B, int N, int d,
+                        solar_dtype t, float* G, void* workspace, size_t workspace_bytes,
+                        void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,142 @@
+// C ABI of the SVD-Attention library: argument validation on the host, workspace
+// carving and kernel launches on the caller's stream.  See include/solar.h.
+#include "../../include/solar.h"
+
+#include <cstdlib>
+
+#include "kernels.h"
+
+namespace {
+
+using namespace solar;
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+bool supported_shape(int d, int r) {
+    if (d != 64 && d != 128 && d != 256) return false;
+    if (r < 1 || r > d || r > 64) return false;
+    if (d == 256 && r > 32) return false;
+    return true;
+}
+
+struct Carve {
+    float* partials;
+    float* G;
+    size_t total;
+};
+
+Carve carve(void* ws, int B, int N, int d) {
+    Carve c;
+    const size_t pbytes = align256(sizeof(float) * gram_partial_floats(B, N, d));
+    const size_t gbytes = align256(sizeof(float) * (size_t)B * d * d);
+    char* base = static_cast<char*>(ws);
+    c.partials = reinterpret_cast<float*>(base);
+    c.G = reinterpret_cast<float*>(base + pbytes);
+    c.total = pbytes + gbytes;
+    return c;
+}
+
+EigParams eig_params_from_env() {
+    EigParams p = eig_default_params();
+    // Debug overrides for tuning the eigen-iteration without a rebuild.
+    if (const char* s = std::getenv("SOLAR_EIG_TOL")) p.tol_res = (float)std::atof(s);
+    if (const char* s = std::getenv("SOLAR_EIG_SWEEPS")) p.sweeps = std::atoi(s);
+    if (const char* s = std::getenv("SOLAR_EIG_MAXIT")) p.max_iter = std::atoi(s);
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* solar_status_string(solar_status s) {
+    switch (s) {
+        case SOLAR_OK: return "ok";
+        case SOLAR_ERR_INVALID_ARG: return "invalid argument";
+        case SOLAR_ERR_UNSUPPORTED: return "unsupported shape or type";
+        case SOLAR_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case SOLAR_ERR_HIP: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+size_t solar_workspace_bytes(int B, int N, int d, int r, int M, solar_dtype t) {
+    (void)r; (void)M; (void)t;
+    if (B <= 0 || N <= 0 || (d != 64 && d != 128 && d != 256)) return 0;
+    return carve(nullptr, B, N, d).total;
+}
+
+solar_status solar_gram(const void* X, const int32_t* lengths, int B, int N, int d, solar_dtype t,
+                        float* G, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X || !G || B <= 0 || N <= 0 || d <= 0) return SOLAR_ERR_INVALID_ARG;
+    if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
+    if (!supported_shape(d, 1)) return SOLAR_ERR_UNSUPPORTED;
+    Carve c = carve(workspace, B, N, d);
+    if (!workspace || workspace_bytes < c.total || ((uintptr_t)workspace & 255)) return SOLAR_ERR_WORKSPACE;
+    hipError_t e = launch_gram(X, lengths, B, N, d, t == SOLAR_BF16, c.partials, G, (hipStream_t)stream);
+    return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
+}
+
+solar_status solar_svd_factorize(const void* X, const int32_t* lengths, int B, int N, int d, int r,
+                                 solar_dtype t, float* S, float* V, float* P, int32_t* info,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X || !S || !V || B <= 0 || N <= 0 || d <= 0 || r <= 0) return SOLAR_ERR_INVALID_ARG;
+    if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
+    if (r > d || r > N) return SOLAR_ERR_INVALID_ARG;
+    if (!supported_shape(d, r)) return SOLAR_ERR_UNSUPPORTED;
+    Carve c = carve(workspace, B, N, d);
+    if (!workspace || workspace_bytes < c.total || ((uintptr_t)workspace & 255)) return SOLAR_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const bool bf16 = t == SOLAR_BF16;
+    hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, st);
+    if (e != hipSuccess) return SOLAR_ERR_HIP;
+    e = launch_eig(c.G, lengths, B, N, d, r, S, V, info, eig_params_from_env(), st);
+    if (e != hipSuccess) return SOLAR_ERR_HIP;
+    if (P) {
+        e = launch_project(X, lengths, V, info, B, N, d, r, bf16, P, st);
+        if (e != hipSuccess) return SOLAR_ERR_HIP;
+    }
+    return SOLAR_OK;
+}
+
+solar_status solar_svd_attention(const void* Q, const float* S, const float* V, const float* P,
+                                 const int32_t* lengths, int B, int N, int d, int r, int M,
+                                 float scale, solar_attn_mode mode, solar_dtype t, float* O,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (!Q || !V || !O || B <= 0 || N <= 0 || d <= 0 || r <= 0 || M <= 0) return SOLAR_ERR_INVALID_ARG;
+    if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
+    if (r > d) return SOLAR_ERR_INVALID_ARG;
+    if (!supported_shape(d, r)) return SOLAR_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    const bool bf16 = t == SOLAR_BF16;
+    hipError_t e;
+    switch (mode) {
+        case SOLAR_ATTN_SEQ_SOFTMAX:
+            if (!P) return SOLAR_ERR_INVALID_ARG;
+            e = launch_attention_seq(Q, V, P, lengths, B, N, d, r, M, scale, bf16, O, st);
+            break;
+        case SOLAR_ATTN_EIGEN_SOFTMAX:
+        case SOLAR_ATTN_LINEAR:
+            if (!S) return SOLAR_ERR_INVALID_ARG;
+            e = launch_attention_tokens(Q, S, V, B, d, r, M, scale, mode == SOLAR_ATTN_EIGEN_SOFTMAX,
+                                        bf16, O, st);
+            break;
+        default:
+            return SOLAR_ERR_INVALID_ARG;
+    }
+    return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
+}
+
+solar_status solar_dense_attention_ref(const void* Q, const void* X, const int32_t* lengths, int B,
+                                       int N, int d, int M, float scale, solar_dtype t, float* O,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (!Q || !X || !O || B <= 0 || N <= 0 || d <= 0 || M <= 0) return SOLAR_ERR_INVALID_ARG;
+    if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
+    if (d > 256) return SOLAR_ERR_UNSUPPORTED;
+    hipError_t e = launch_dense_ref(Q, X, lengths, B, N, d, M, scale, t == SOLAR_BF16, O, (hipStream_t)stream);
+    return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
+}
+
+}  // extern "C"

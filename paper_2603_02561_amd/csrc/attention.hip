@@ -1,0 +1,352 @@
+// SVD-Attention, Attn_SVD = MatMul(MatMul(Query, Key_r^T), Value_r) (Section
+// "SVD-Attention"), on gfx950.
+//
+// attention_seq_kernel -- softmax over the N sequence positions, evaluated in
+// factor space:   O = softmax_n(scale * Qt P^T) P V^T,   Qt = Q V,  P = X V.
+// The M x N score matrix is never stored: the kernel walks over tiles of P with an
+// online softmax (running row maximum and row sum), keeps Z = sum_n w_n P_n in the
+// matrix-unit accumulators and only at the end maps Z / l back to d columns with
+// V^T.  Key and value are the same tile of P, so one LDS tile feeds both products.
+// All three products use the float 16x16x4 MFMA, whose operands are single values
+// per lane; the transposed forms S^T = P Qt^T and Z^T = P^T W^T are used so that a
+// query is a lane (column l%16 of every accumulator): the softmax statistics of a
+// query are then combined over 4 lane groups only, and the accumulator of one
+// product is directly the B operand of the next with no data movement (the
+// contraction index may be enumerated in any order as long as A and B agree).
+//
+// attention_tokens_kernel -- the literal r-token form, with or without softmax:
+//   O = softmax_k(scale * Q T^T) T   or   O = scale * (Q T^T) T,   T = diag(S) V^T.
+#include "common.h"
+#include "kernels.h"
+
+namespace solar {
+
+namespace {
+
+constexpr int kAttnThreads = 256;
+constexpr int kQB = 2;    // 16-query blocks per wave
+constexpr int kNT = 64;   // rows of P per tile
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Accumulator component (lane group g, register t) of a 16-row output block is
+// bound to rank index g + 4*t of the block instead of 4*g + t: with this choice the
+// four lane groups read four consecutive floats of an LDS row when the accumulator
+// is reused as a B operand, which keeps those reads free of bank conflicts.
+__device__ __forceinline__ int rank_perm(int i) { return (i >> 2) + 4 * (i & 3); }
+
+template <int D, int RB, bool BF16>
+__global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
+    const void* __restrict__ Qv, const float* __restrict__ V, const float* __restrict__ P,
+    const int32_t* __restrict__ lengths, int N, int r, int M, float scale, float* __restrict__ O) {
+    constexpr int RP = 16 * RB;
+    constexpr int LDV = RP + 4;
+    constexpr int LDP = RP + 4;
+    extern __shared__ float smem[];
+    float* Vs = smem;                       // [D][LDV]
+    float* Ps = Vs + D * LDV;               // [2][kNT][LDP]
+    const int b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i16 = lane & 15, g = lane >> 4;
+    const int len = user_len(lengths, b, N);
+    const int m_wave = blockIdx.x * (4 * kQB * 16) + wave * (kQB * 16);
+    const float* Pb = P + (size_t)b * N * r;
+
+    for (int e = tid; e < D * RP; e += kAttnThreads) {
+        const int k = e / RP, c = e % RP;
+        Vs[k * LDV + c] = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
+    }
+    // zero both P tiles once so that the padded rank columns stay zero
+    for (int e = tid; e < 2 * kNT * LDP; e += kAttnThreads) Ps[e] = 0.f;
+    __syncthreads();
+
+    // ---- prologue: Qt^T = V^T Q^T, scaled by scale*log2(e) -------------------------
+    v4f qt[kQB][RB];
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) {
+#pragma unroll
+        for (int ib = 0; ib < RB; ++ib) qt[qb][ib] = v4f{0.f, 0.f, 0.f, 0.f};
+        const int m = m_wave + 16 * qb + i16;
+        const bool valid = m < M;
+        const size_t row = ((size_t)b * M + (valid ? m : 0)) * D;
+        for (int kk = 0; kk < D / 16; ++kk) {
+            v4f q4;
+            if constexpr (BF16) {
+                uint2 w = reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(Qv) + row)[4 * kk + g];
+                q4 = v4f{bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y)};
+            } else {
+                q4 = reinterpret_cast<const v4f*>(reinterpret_cast<const float*>(Qv) + row)[4 * kk + g];
+            }
+            if (!valid) q4 = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float* vrow = Vs + (16 * kk + 4 * g + t) * LDV;
+#pragma unroll
+                for (int ib = 0; ib < RB; ++ib)
+                    qt[qb][ib] = mfma16x16x4(vrow[16 * ib + rank_perm(i16)], q4[t], qt[qb][ib]);
+            }
+        }
+#pragma unroll
+        for (int ib = 0; ib < RB; ++ib) qt[qb][ib] *= scale * kLog2e;
+    }
+
+    // ---- main loop over tiles of P -------------------------------------------------
+    v4f z[kQB][RB];
+    float mrun[kQB], lrun[kQB];
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) {
+        mrun[qb] = -INFINITY;
+        lrun[qb] = 0.f;
+#pragma unroll
+        for (int ib = 0; ib < RB; ++ib) z[qb][ib] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int ntiles = ceil_div(len, kNT);
+    // A tile is kNT*r consecutive floats of P; each thread moves `kLoads` float4 (r % 4 == 0)
+    // or falls back to scalars.
+    auto load_tile = [&](int tile, float* dst) {
+        const int n0 = tile * kNT;
+        if ((r & 3) == 0) {
+            const int quads_per_row = r >> 2;
+            for (int e = tid; e < kNT * quads_per_row; e += kAttnThreads) {
+                const int nn = e / quads_per_row, c4 = e % quads_per_row;
+                v4f v = v4f{0.f, 0.f, 0.f, 0.f};
+                if (n0 + nn < len) v = *reinterpret_cast<const v4f*>(Pb + (size_t)(n0 + nn) * r + 4 * c4);
+                *reinterpret_cast<v4f*>(dst + nn * LDP + 4 * c4) = v;
+            }
+        } else {
+            for (int e = tid; e < kNT * r; e += kAttnThreads) {
+                const int nn = e / r, c = e % r;
+                dst[nn * LDP + c] = (n0 + nn < len) ? Pb[(size_t)(n0 + nn) * r + c] : 0.f;
+            }
+        }
+    };
+    if (ntiles > 0) load_tile(0, Ps);
+    __syncthreads();
+
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const float* pt = Ps + (tile & 1) * (kNT * LDP);
+        if (tile + 1 < ntiles) load_tile(tile + 1, Ps + ((tile + 1) & 1) * (kNT * LDP));
+        const int n0 = tile * kNT;
+
+        // scores S^T[n][m] for the 4 blocks of 16 rows
+        v4f s[kQB][kNT / 16];
+#pragma unroll
+        for (int nb = 0; nb < kNT / 16; ++nb) {
+#pragma unroll
+            for (int qb = 0; qb < kQB; ++qb) s[qb][nb] = v4f{0.f, 0.f, 0.f, 0.f};
+            const float* prow = pt + (16 * nb + i16) * LDP;
+#pragma unroll
+            for (int ib = 0; ib < RB; ++ib)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float a = prow[16 * ib + 4 * t + g];
+#pragma unroll
+                    for (int qb = 0; qb < kQB; ++qb)
+                        s[qb][nb] = mfma16x16x4(a, qt[qb][ib][t], s[qb][nb]);
+                }
+        }
+        // mask rows past the valid length (component t of block nb is row 16*nb + 4*g + t)
+        if (n0 + kNT > len) {
+#pragma unroll
+            for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (n0 + 16 * nb + 4 * g + t >= len) {
+#pragma unroll
+                        for (int qb = 0; qb < kQB; ++qb) s[qb][nb][t] = -INFINITY;
+                    }
+        }
+        // online softmax per query (= per lane column), weights overwrite the scores
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) {
+            float mt = -INFINITY;
+#pragma unroll
+            for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) mt = fmaxf(mt, s[qb][nb][t]);
+            mt = wave_xor_max(mt, 16);
+            mt = wave_xor_max(mt, 32);
+            const float mnew = fmaxf(mrun[qb], mt);   // finite: row 0 of tile 0 is valid
+            const float alpha = exp2f(mrun[qb] - mnew);
+            mrun[qb] = mnew;
+            float lsum = 0.f;
+#pragma unroll
+            for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float w = exp2f(s[qb][nb][t] - mnew);
+                    s[qb][nb][t] = w;
+                    lsum += w;
+                }
+            lrun[qb] = lrun[qb] * alpha + lsum;
+#pragma unroll
+            for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= alpha;
+        }
+        // Z^T += P^T W^T : contraction slot g of step (nb, t) is row 16*nb + 4*g + t
+#pragma unroll
+        for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float* prow = pt + (16 * nb + 4 * g + t) * LDP;
+#pragma unroll
+                for (int ib = 0; ib < RB; ++ib) {
+                    const float a = prow[16 * ib + rank_perm(i16)];
+#pragma unroll
+                    for (int qb = 0; qb < kQB; ++qb)
+                        z[qb][ib] = mfma16x16x4(a, s[qb][nb][t], z[qb][ib]);
+                }
+            }
+        __syncthreads();
+    }
+
+    // ---- epilogue: O^T = V (Z / l)^T ------------------------------------------------
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) {
+        float l = lrun[qb];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+#pragma unroll
+        for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= inv;
+        const int m = m_wave + 16 * qb + i16;
+        for (int cb = 0; cb < D / 16; ++cb) {
+            v4f o = v4f{0.f, 0.f, 0.f, 0.f};
+            const float* vrow = Vs + (16 * cb + i16) * LDV;
+#pragma unroll
+            for (int ib = 0; ib < RB; ++ib)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    o = mfma16x16x4(vrow[16 * ib + 4 * t + g], z[qb][ib][t], o);
+            if (m < M) *reinterpret_cast<v4f*>(O + ((size_t)b * M + m) * D + 16 * cb + 4 * g) = o;
+        }
+    }
+}
+
+// Literal r-token form.  One wave per candidate at a time; lane k holds token k.
+template <bool BF16>
+__global__ __launch_bounds__(256) void attention_tokens_kernel(
+    const void* __restrict__ Qv, const float* __restrict__ S, const float* __restrict__ V, int d,
+    int r, int M, float scale, int softmax, float* __restrict__ O) {
+    extern __shared__ float smem[];
+    const int LDT = d + 1;
+    float* T = smem;               // [r][LDT]  T[k][j] = S[k] V[j][k]
+    const int b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int e = tid; e < d * r; e += 256) {
+        const int j = e / r, k = e % r;
+        T[k * LDT + j] = S[(size_t)b * r + k] * V[((size_t)b * d + j) * r + k];
+    }
+    __syncthreads();
+    const int rows_per_block = 64;
+    for (int mi = wave; mi < rows_per_block; mi += 4) {
+        const int m = blockIdx.x * rows_per_block + mi;
+        if (m >= M) break;   // uniform over the wave
+        // lane holds q[lane], q[lane+64], ... ; values are handed round with shuffles
+        float qreg[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int j = lane + 64 * c;
+            qreg[c] = 0.f;
+            if (j < d) {
+                const size_t idx = ((size_t)b * M + m) * d + j;
+                qreg[c] = BF16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(Qv)[idx] << 16)
+                               : reinterpret_cast<const float*>(Qv)[idx];
+            }
+        }
+        float sc = 0.f;
+        const float* tk = T + (lane < r ? lane : 0) * LDT;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (64 * c < d)
+                for (int jj = 0; jj < 64; ++jj) sc += __shfl(qreg[c], jj) * tk[64 * c + jj];
+        sc *= scale;
+        float w;
+        if (softmax) {
+            float mx = lane < r ? sc : -INFINITY;
+            for (int msk = 1; msk < 64; msk <<= 1) mx = fmaxf(mx, __shfl_xor(mx, msk));
+            float ex = lane < r ? exp2f((sc - mx) * kLog2e) : 0.f;
+            float sum = ex;
+            for (int msk = 1; msk < 64; msk <<= 1) sum += __shfl_xor(sum, msk);
+            w = ex / sum;
+        } else {
+            w = lane < r ? sc : 0.f;
+        }
+        for (int j = lane; j < d; j += 64) {
+            float acc = 0.f;
+            for (int k = 0; k < r; ++k) acc += __shfl(w, k) * T[k * LDT + j];
+            O[((size_t)b * M + m) * d + j] = acc;
+        }
+    }
+}
+
+}  // namespace
+
+template <int D, int RB>
+static hipError_t launch_seq_t(const void* Q, const float* V, const float* P,
+                               const int32_t* lengths, int B, int N, int r, int M, float scale,
+                               bool bf16, float* O, hipStream_t stream) {
+    constexpr int RP = 16 * RB;
+    const size_t lds = sizeof(float) * ((size_t)D * (RP + 4) + 2 * kNT * (RP + 4));
+    dim3 grid(ceil_div(M, 4 * kQB * 16), B), block(kAttnThreads);
+    if (bf16) {
+        auto kern = attention_seq_kernel<D, RB, true>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, N, r, M, scale, O);
+    } else {
+        auto kern = attention_seq_kernel<D, RB, false>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, N, r, M, scale, O);
+    }
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_seq_d(const void* Q, const float* V, const float* P,
+                               const int32_t* lengths, int B, int N, int r, int M, float scale,
+                               bool bf16, float* O, hipStream_t stream) {
+    switch ((r + 15) / 16) {
+        case 1: return launch_seq_t<D, 1>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        case 2: return launch_seq_t<D, 2>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        case 3: return launch_seq_t<D, 3>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        case 4: return launch_seq_t<D, 4>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_attention_seq(const void* Q, const float* V, const float* P,
+                                const int32_t* lengths, int B, int N, int d, int r, int M,
+                                float scale, bool bf16, float* O, hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_seq_d<64>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        case 128: return launch_seq_d<128>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        case 256: return launch_seq_d<256>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_attention_tokens(const void* Q, const float* S, const float* V, int B, int d,
+                                   int r, int M, float scale, bool softmax, bool bf16, float* O,
+                                   hipStream_t stream) {
+    const size_t lds = sizeof(float) * ((size_t)r * (d + 1));
+    dim3 grid(ceil_div(M, 64), B), block(256);
+    if (bf16) {
+        auto kern = attention_tokens_kernel<true>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, d, r, M, scale, softmax ? 1 : 0, O);
+    } else {
+        auto kern = attention_tokens_kernel<false>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, d, r, M, scale, softmax ? 1 : 0, O);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace solar

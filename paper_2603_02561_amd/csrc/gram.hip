@@ -1,0 +1,243 @@
+// Gram contraction over the sequence axis, G_b = X_b^T X_b (the product that the
+// power iteration of Algorithm 1 applies to Omega), for gfx950.
+//
+// The sequence axis is the slow memory axis of the row-major X, so it is the
+// contraction (K) axis of the MFMA while both operands come from the same rows.
+// A wave streams whole rows with 16 lanes per row and CPL = d/16 consecutive
+// columns per lane; column CPL*j + s of lane j becomes "fragment s", and fragment
+// pair (s1 <= s2) yields the 16x16 block {G[CPL*i+s1][CPL*j+s2]}.  Only the upper
+// triangle of fragment pairs is formed.  For bf16 the eight rows a lane loads are
+// transposed in registers into the k-contiguous operand the 16x16x32 MFMA wants;
+// for float the 16x16x4 MFMA takes the loaded values as they are.  No LDS is used
+// in the streaming loop: every byte of X is read from HBM once, by one wave.
+//
+// The sequence is cut into `nsplit` chunks per user (one workgroup each); the
+// waves of a workgroup add their accumulators in LDS in a fixed order, the
+// per-chunk partial blocks go to the workspace, and gram_finalize_kernel adds them
+// in a fixed order and undoes the fragment permutation.  Results are therefore
+// bitwise reproducible.
+#include "common.h"
+#include "kernels.h"
+
+namespace solar {
+
+template <int CPL>
+__host__ __device__ constexpr int gram_pairs() { return CPL * (CPL + 1) / 2; }
+
+constexpr int kGramWaves = 4;
+
+template <int CPL, bool BF16>
+__global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
+    const void* __restrict__ Xv, const int32_t* __restrict__ lengths, int N, int nsplit,
+    float* __restrict__ partials) {
+    constexpr int D = 16 * CPL;
+    constexpr int NP = gram_pairs<CPL>();
+    constexpr int STEP = BF16 ? 32 : 16;  // rows a wave consumes per step
+    const int b = blockIdx.y;
+    const int split = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int j = lane & 15;
+    const int h = lane >> 4;
+    const int len = user_len(lengths, b, N);
+    int chunk = ceil_div(ceil_div(len, nsplit), STEP) * STEP;
+    const int r0 = split * chunk;
+    const int r1 = min(len, r0 + chunk);
+
+    v4f acc[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) acc[p] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    if constexpr (BF16) {
+        constexpr int W = CPL / 2;  // 32-bit words per lane per row
+        const uint32_t* X = reinterpret_cast<const uint32_t*>(Xv) + (size_t)b * N * (D / 2);
+        uint32_t cur[8][W], nxt[8][W];
+        auto load = [&](uint32_t (&dst)[8][W], int base) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int row = base + 8 * h + t;
+                if (row < r1) {
+                    const uint32_t* p = X + (size_t)row * (D / 2) + W * j;
+                    if constexpr (W == 4) {
+                        v4u v = *reinterpret_cast<const v4u*>(p);
+                        dst[t][0] = v.x; dst[t][1] = v.y; dst[t][2] = v.z; dst[t][3] = v.w;
+                    } else if constexpr (W == 2) {
+                        uint2 v = *reinterpret_cast<const uint2*>(p);
+                        dst[t][0] = v.x; dst[t][1] = v.y;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < W / 4; ++q) {
+                            v4u v = *reinterpret_cast<const v4u*>(p + 4 * q);
+                            dst[t][4 * q + 0] = v.x; dst[t][4 * q + 1] = v.y;
+                            dst[t][4 * q + 2] = v.z; dst[t][4 * q + 3] = v.w;
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int w = 0; w < W; ++w) dst[t][w] = 0u;
+                }
+            }
+        };
+        int base = r0 + wave * STEP;
+        if (base < r1) load(cur, base);
+        while (base < r1) {
+            const int nbase = base + kGramWaves * STEP;
+            if (nbase < r1) load(nxt, nbase);
+            // 8x(2W) transpose of 16-bit elements: fragment s holds column CPL*j+s of the
+            // lane's eight rows, two rows per word.
+            v4u frag[CPL];
+#pragma unroll
+            for (int s = 0; s < CPL; ++s) {
+                uint32_t o[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t a = cur[2 * u][s / 2], c = cur[2 * u + 1][s / 2];
+                    o[u] = (s & 1) ? ((a >> 16) | (c & 0xffff0000u)) : ((a & 0xffffu) | (c << 16));
+                }
+                frag[s] = v4u{o[0], o[1], o[2], o[3]};
+            }
+            int p = 0;
+#pragma unroll
+            for (int s1 = 0; s1 < CPL; ++s1)
+#pragma unroll
+                for (int s2 = s1; s2 < CPL; ++s2) {
+                    acc[p] = mfma16x16x32bf16(frag[s1], frag[s2], acc[p]);
+                    ++p;
+                }
+            if (nbase < r1) {
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+#pragma unroll
+                    for (int w = 0; w < W; ++w) cur[t][w] = nxt[t][w];
+            }
+            base = nbase;
+        }
+    } else {
+        const float* X = reinterpret_cast<const float*>(Xv) + (size_t)b * N * D;
+        float cur[4][CPL], nxt[4][CPL];
+        auto load = [&](float (&dst)[4][CPL], int base) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int row = base + 4 * t + h;
+                if (row < r1) {
+                    const float* p = X + (size_t)row * D + CPL * j;
+#pragma unroll
+                    for (int q = 0; q < CPL / 4; ++q) {
+                        v4f v = *reinterpret_cast<const v4f*>(p + 4 * q);
+                        dst[t][4 * q + 0] = v.x; dst[t][4 * q + 1] = v.y;
+                        dst[t][4 * q + 2] = v.z; dst[t][4 * q + 3] = v.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int s = 0; s < CPL; ++s) dst[t][s] = 0.f;
+                }
+            }
+        };
+        int base = r0 + wave * STEP;
+        if (base < r1) load(cur, base);
+        while (base < r1) {
+            const int nbase = base + kGramWaves * STEP;
+            if (nbase < r1) load(nxt, nbase);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                int p = 0;
+#pragma unroll
+                for (int s1 = 0; s1 < CPL; ++s1)
+#pragma unroll
+                    for (int s2 = s1; s2 < CPL; ++s2) {
+                        acc[p] = mfma16x16x4(cur[t][s1], cur[t][s2], acc[p]);
+                        ++p;
+                    }
+            }
+            if (nbase < r1) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int s = 0; s < CPL; ++s) cur[t][s] = nxt[t][s];
+            }
+            base = nbase;
+        }
+    }
+
+    // Fixed-order sum over the waves of the workgroup, then one coalesced store.
+    __shared__ v4f red[NP * 64];
+    for (int w = 0; w < kGramWaves; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                if (w == 0) red[p * 64 + lane] = acc[p];
+                else red[p * 64 + lane] += acc[p];
+            }
+        }
+        __syncthreads();
+    }
+    v4f* out = reinterpret_cast<v4f*>(partials) + ((size_t)b * nsplit + split) * (NP * 64);
+    for (int i = threadIdx.x; i < NP * 64; i += kGramWaves * 64) out[i] = red[i];
+}
+
+// G[b][a][c] = sum over chunks of the partial block element that holds (a, c) or,
+// below the diagonal of fragment pairs, its mirror image (c, a).
+template <int CPL>
+__global__ __launch_bounds__(256) void gram_finalize_kernel(const float* __restrict__ partials,
+                                                            int nsplit, float* __restrict__ G) {
+    constexpr int D = 16 * CPL;
+    constexpr int NP = gram_pairs<CPL>();
+    const int b = blockIdx.y;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= D * D) return;
+    int a = e / D, c = e % D;
+    int s1 = a % CPL, i1 = a / CPL, s2 = c % CPL, i2 = c / CPL;
+    if (s1 > s2) {
+        int t = s1; s1 = s2; s2 = t;
+        t = i1; i1 = i2; i2 = t;
+    }
+    const int pair = s1 * CPL - (s1 * (s1 - 1)) / 2 + (s2 - s1);
+    const int off = pair * 256 + (i2 + 16 * (i1 / 4)) * 4 + (i1 % 4);
+    const float* p = partials + (size_t)b * nsplit * (NP * 256) + off;
+    float acc = 0.f;
+    for (int s = 0; s < nsplit; ++s) acc += p[(size_t)s * (NP * 256)];
+    G[(size_t)b * D * D + e] = acc;
+}
+
+int gram_nsplit(int B, int N) {
+    // Aim at about two workgroups per compute unit, at least 512 rows per chunk.
+    int want = ceil_div(512, B);
+    int cap = ceil_div(N, 512);
+    int n = want < cap ? want : cap;
+    if (n < 1) n = 1;
+    if (n > 64) n = 64;
+    return n;
+}
+
+size_t gram_partial_floats(int B, int N, int d) {
+    const int cpl = d / 16;
+    return (size_t)B * gram_nsplit(B, N) * (cpl * (cpl + 1) / 2) * 256;
+}
+
+template <int CPL>
+static hipError_t launch_gram_t(const void* X, const int32_t* lengths, int B, int N, bool bf16,
+                                float* partials, float* G, hipStream_t stream) {
+    const int nsplit = gram_nsplit(B, N);
+    dim3 grid(nsplit, B), block(kGramWaves * 64);
+    if (bf16)
+        hipLaunchKernelGGL((gram_partial_kernel<CPL, true>), grid, block, 0, stream, X, lengths, N,
+                           nsplit, partials);
+    else
+        hipLaunchKernelGGL((gram_partial_kernel<CPL, false>), grid, block, 0, stream, X, lengths, N,
+                           nsplit, partials);
+    constexpr int D = 16 * CPL;
+    dim3 g2(ceil_div(D * D, 256), B);
+    hipLaunchKernelGGL((gram_finalize_kernel<CPL>), g2, dim3(256), 0, stream, partials, nsplit, G);
+    return hipGetLastError();
+}
+
+hipError_t launch_gram(const void* X, const int32_t* lengths, int B, int N, int d, bool bf16,
+                       float* partials, float* G, hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_gram_t<4>(X, lengths, B, N, bf16, partials, G, stream);
+        case 128: return launch_gram_t<8>(X, lengths, B, N, bf16, partials, G, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace solar

@@ -1,0 +1,46 @@
+// Host-side launchers of the gfx950 kernels (internal to the library).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace solar {
+
+// gram.hip
+int gram_nsplit(int B, int N);
+size_t gram_partial_floats(int B, int N, int d);
+hipError_t launch_gram(const void* X, const int32_t* lengths, int B, int N, int d, bool bf16,
+                       float* partials, float* G, hipStream_t stream);
+
+// eig.hip
+struct EigParams {
+    float tol_res;      // residual tolerance relative to the largest Ritz value
+    float tol_orth;     // a sweep whose largest |cos| is below this ends the Jacobi phase
+    int max_iter;       // cap on power steps
+    int sweeps;         // cap on Jacobi sweeps per power step
+};
+EigParams eig_default_params();
+int eig_block_columns(int d, int r);
+size_t eig_lds_bytes(int d, int r);
+hipError_t launch_eig(const float* G, const int32_t* lengths, int B, int N, int d, int r, float* S,
+                      float* V, int32_t* info, const EigParams& prm, hipStream_t stream);
+
+// project.hip
+hipError_t launch_project(const void* X, const int32_t* lengths, const float* V,
+                          const int32_t* info, int B, int N, int d, int r, bool bf16, float* P,
+                          hipStream_t stream);
+
+// attention.hip
+hipError_t launch_attention_seq(const void* Q, const float* V, const float* P,
+                                const int32_t* lengths, int B, int N, int d, int r, int M,
+                                float scale, bool bf16, float* O, hipStream_t stream);
+hipError_t launch_attention_tokens(const void* Q, const float* S, const float* V, int B, int d,
+                                   int r, int M, float scale, bool softmax, bool bf16, float* O,
+                                   hipStream_t stream);
+
+// dense_ref.hip
+hipError_t launch_dense_ref(const void* Q, const void* X, const int32_t* lengths, int B, int N,
+                            int d, int M, float scale, bool bf16, float* O, hipStream_t stream);
+
+}  // namespace solar
