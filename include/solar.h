@@ -136,6 +136,19 @@ solar_status solar_gram(const void* X, const int32_t* lengths, int B, int N, int
                         solar_dtype t, float* G, void* workspace, size_t workspace_bytes,
                         void* stream);
 
+/*
+ * Per-phase timing of solar_svd_factorize, for benchmarks.  After
+ * solar_phase_timing_begin() every factorize call (up to 256 of them) records HIP
+ * events on its stream around its three phases: the Gram contraction, the
+ * eigen-iteration and the projection (Algorithm 1's power-iteration product, its
+ * basis/small-SVD steps, and P = X V).  solar_phase_timing_end() waits for the
+ * last of them, stores the summed milliseconds of each phase in ms_sum[0..2]
+ * (HOST memory, may be NULL), switches the timing off and returns the number of
+ * calls that were timed.  Not thread-safe; one stream at a time.
+ */
+void solar_phase_timing_begin(void);
+int solar_phase_timing_end(float* ms_sum);
+
 #ifdef __cplusplus
 }
 #endif

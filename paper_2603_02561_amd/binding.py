@@ -43,6 +43,10 @@ _lib.solar_svd_attention.restype = _ci
 _lib.solar_dense_attention_ref.argtypes = [_vp, _vp, _vp, _ci, _ci, _ci, _ci, _cf, _ci, _vp, _vp,
                                            _sz, _vp]
 _lib.solar_dense_attention_ref.restype = _ci
+_lib.solar_phase_timing_begin.argtypes = []
+_lib.solar_phase_timing_begin.restype = None
+_lib.solar_phase_timing_end.argtypes = [ctypes.POINTER(ctypes.c_float)]
+_lib.solar_phase_timing_end.restype = _ci
 
 
 class SolarError(RuntimeError):
@@ -79,6 +83,17 @@ def solar_status_string(code: int) -> str:
 
 def solar_workspace_bytes(B: int, N: int, d: int, r: int, M: int, dtype_code: int) -> int:
     return int(_lib.solar_workspace_bytes(B, N, d, r, M, dtype_code))
+
+
+def solar_phase_timing_begin() -> None:
+    _lib.solar_phase_timing_begin()
+
+
+def solar_phase_timing_end():
+    """Returns (calls, [gram_ms, eig_ms, project_ms]) summed over the timed calls."""
+    buf = (ctypes.c_float * 3)()
+    n = _lib.solar_phase_timing_end(buf)
+    return int(n), [float(buf[i]) for i in range(3)]
 
 
 def solar_gram(X, lengths, G, workspace, raise_on_error: bool = True) -> int:

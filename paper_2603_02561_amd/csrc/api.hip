@@ -36,12 +36,33 @@ Carve carve(void* ws, int B, int N, int d) {
     return c;
 }
 
+// Optional per-phase timing of solar_svd_factorize: HIP events recorded on the
+// caller's stream at the phase boundaries.  Host-side bookkeeping only.
+struct PhaseTimer {
+    static constexpr int kMaxCalls = 256;
+    bool enabled = false;
+    int calls = 0;
+    hipEvent_t ev[kMaxCalls][4];
+    int created = 0;
+};
+PhaseTimer g_timer;
+
+void timer_mark(int call, int slot, hipStream_t st) {
+    if (!g_timer.enabled || call >= PhaseTimer::kMaxCalls) return;
+    while (g_timer.created <= call) {
+        for (int i = 0; i < 4; ++i) (void)hipEventCreate(&g_timer.ev[g_timer.created][i]);
+        ++g_timer.created;
+    }
+    (void)hipEventRecord(g_timer.ev[call][slot], st);
+}
+
 EigParams eig_params_from_env() {
     EigParams p = eig_default_params();
     // Debug overrides for tuning the eigen-iteration without a rebuild.
     if (const char* s = std::getenv("SOLAR_EIG_TOL")) p.tol_res = (float)std::atof(s);
     if (const char* s = std::getenv("SOLAR_EIG_SWEEPS")) p.sweeps = std::atoi(s);
     if (const char* s = std::getenv("SOLAR_EIG_MAXIT")) p.max_iter = std::atoi(s);
+    if (const char* s = std::getenv("SOLAR_EIG_DEBUG")) p.debug_counts = std::atoi(s);
     return p;
 }
 
@@ -66,6 +87,27 @@ size_t solar_workspace_bytes(int B, int N, int d, int r, int M, solar_dtype t) {
     return carve(nullptr, B, N, d).total;
 }
 
+void solar_phase_timing_begin(void) {
+    g_timer.enabled = true;
+    g_timer.calls = 0;
+}
+
+int solar_phase_timing_end(float* ms_sum) {
+    const int n = g_timer.calls;
+    float acc[3] = {0.f, 0.f, 0.f};
+    for (int c = 0; c < n; ++c) {
+        (void)hipEventSynchronize(g_timer.ev[c][3]);
+        for (int i = 0; i < 3; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, g_timer.ev[c][i], g_timer.ev[c][i + 1]) == hipSuccess) acc[i] += ms;
+        }
+    }
+    if (ms_sum) for (int i = 0; i < 3; ++i) ms_sum[i] = acc[i];
+    g_timer.enabled = false;
+    g_timer.calls = 0;
+    return n;
+}
+
 solar_status solar_gram(const void* X, const int32_t* lengths, int B, int N, int d, solar_dtype t,
                         float* G, void* workspace, size_t workspace_bytes, void* stream) {
     if (!X || !G || B <= 0 || N <= 0 || d <= 0) return SOLAR_ERR_INVALID_ARG;
@@ -88,14 +130,20 @@ solar_status solar_svd_factorize(const void* X, const int32_t* lengths, int B, i
     if (!workspace || workspace_bytes < c.total || ((uintptr_t)workspace & 255)) return SOLAR_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const bool bf16 = t == SOLAR_BF16;
+    const int call = g_timer.calls;
+    timer_mark(call, 0, st);
     hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, st);
     if (e != hipSuccess) return SOLAR_ERR_HIP;
+    timer_mark(call, 1, st);
     e = launch_eig(c.G, lengths, B, N, d, r, S, V, info, eig_params_from_env(), st);
     if (e != hipSuccess) return SOLAR_ERR_HIP;
+    timer_mark(call, 2, st);
     if (P) {
         e = launch_project(X, lengths, V, info, B, N, d, r, bf16, P, st);
         if (e != hipSuccess) return SOLAR_ERR_HIP;
     }
+    timer_mark(call, 3, st);
+    if (g_timer.enabled && call < PhaseTimer::kMaxCalls) g_timer.calls = call + 1;
     return SOLAR_OK;
 }
 
@@ -114,7 +162,12 @@ solar_status solar_svd_attention(const void* Q, const float* S, const float* V, 
     switch (mode) {
         case SOLAR_ATTN_SEQ_SOFTMAX:
             if (!P) return SOLAR_ERR_INVALID_ARG;
-            e = launch_attention_seq(Q, V, P, lengths, B, N, d, r, M, scale, bf16, O, st);
+            // bf16 inputs take the bf16 matrix-unit path (split operands, about 16 mantissa
+            // bits in the scores); float inputs keep float arithmetic throughout
+            if (bf16 && attention_seq_bf16_supported(d, r) && !std::getenv("SOLAR_ATTN_F32"))
+                e = launch_attention_seq_bf16(Q, V, P, lengths, B, N, d, r, M, scale, bf16, O, st);
+            else
+                e = launch_attention_seq(Q, V, P, lengths, B, N, d, r, M, scale, bf16, O, st);
             break;
         case SOLAR_ATTN_EIGEN_SOFTMAX:
         case SOLAR_ATTN_LINEAR:

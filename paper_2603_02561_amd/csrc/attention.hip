@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
     constexpr int RP = 16 * RB;
     constexpr int LDV = RP + 4;
     constexpr int LDP = RP + 4;
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                       // [D][LDV]
     float* Ps = Vs + D * LDV;               // [2][kNT][LDP]
     const int b = blockIdx.y;
@@ -167,14 +167,14 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
             mt = wave_xor_max(mt, 16);
             mt = wave_xor_max(mt, 32);
             const float mnew = fmaxf(mrun[qb], mt);   // finite: row 0 of tile 0 is valid
-            const float alpha = exp2f(mrun[qb] - mnew);
+            const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - mnew);
             mrun[qb] = mnew;
             float lsum = 0.f;
 #pragma unroll
             for (int nb = 0; nb < kNT / 16; ++nb)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const float w = exp2f(s[qb][nb][t] - mnew);
+                    const float w = __builtin_amdgcn_exp2f(s[qb][nb][t] - mnew);
                     s[qb][nb][t] = w;
                     lsum += w;
                 }
@@ -227,7 +227,7 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void attention_tokens_kernel(
     const void* __restrict__ Qv, const float* __restrict__ S, const float* __restrict__ V, int d,
     int r, int M, float scale, int softmax, float* __restrict__ O) {
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const int LDT = d + 1;
     float* T = smem;               // [r][LDT]  T[k][j] = S[k] V[j][k]
     const int b = blockIdx.y;
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256) void attention_tokens_kernel(
         if (softmax) {
             float mx = lane < r ? sc : -INFINITY;
             for (int msk = 1; msk < 64; msk <<= 1) mx = fmaxf(mx, __shfl_xor(mx, msk));
-            float ex = lane < r ? exp2f((sc - mx) * kLog2e) : 0.f;
+            float ex = lane < r ? __builtin_amdgcn_exp2f((sc - mx) * kLog2e) : 0.f;
             float sum = ex;
             for (int msk = 1; msk < 64; msk <<= 1) sum += __shfl_xor(sum, msk);
             w = ex / sum;

@@ -1,0 +1,349 @@
+// SVD-Attention in its sequence-softmax form, O = softmax_n(scale * Qt P^T) P V^T
+// (Section "SVD-Attention"; Qt = Q V, P = X V), fast path for bf16 inputs on the
+// bf16 matrix unit of gfx950.
+//
+// P and Qt are float quantities derived from the factorization, and the scores are
+// exponentiated, so they are not simply rounded to bf16: each is split into a bf16
+// head and a bf16 tail (x = hi + lo, |lo| <= 2^-9 |hi|) and the score product uses
+// the three leading cross terms, hi*hi + lo*hi + hi*lo, accumulated in float by the
+// 16x16x32 MFMA: the scores carry about 16 mantissa bits.  The softmax weights are
+// rounded to bf16 once and multiplied into hi + lo of P (two MFMAs); the row sum of
+// the *rounded* weights is produced by one more MFMA against a tile of ones, so the
+// normalization is consistent with the weights actually used and needs neither a
+// VALU add per score nor a cross-lane reduction.
+//
+// As in the float kernel the products are evaluated transposed (S^T = P Qt^T,
+// Z^T = P^T W^T) so that a query is a lane: accumulators of one product are the B
+// operand of the next without any data movement, because the contraction index can
+// be enumerated in any order as long as both operands agree.  The A operands come
+// from two LDS images of the current tile of P that the loader writes while it
+// splits the tile: row-major (contraction over the rank index, for the scores) and
+// transposed (contraction over the sequence index, for Z).
+//
+// The kernel is bound by the vector ALU: per score one max, one subtract, one exp2
+// (transcendental rate) and half a pack instruction, against 5/16 of a 16-cycle MFMA.
+// Eight waves per workgroup (two per SIMD) let the matrix unit of one wave run
+// under the exponentials of the other.
+#include "common.h"
+#include "kernels.h"
+
+namespace solar {
+
+namespace {
+
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kQB = 2;    // 16-query blocks per wave
+constexpr int kNT = 64;   // rows of P per tile
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    // round to nearest even; inputs are finite
+    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+    v2bf v = {(__bf16)a, (__bf16)b};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ void split_bf16(float x, float& hi, float& lo) {
+    hi = (float)(__bf16)x;
+    lo = x - hi;
+}
+
+template <int D, int RB2, bool BF16>
+__global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
+    const void* __restrict__ Qv, const float* __restrict__ V, const float* __restrict__ P,
+    const int32_t* __restrict__ lengths, int N, int r, int M, float scale, float* __restrict__ O) {
+    constexpr int RP = 32 * RB2;          // padded rank
+    constexpr int RB = RP / 16;
+    constexpr int LDV = RP + 4;           // floats
+    constexpr int LDR = RP + 8;           // bf16 elements, row-major image  [kNT][LDR]
+    constexpr int LDT = kNT + 8;          // bf16 elements, transposed image [RP][LDT]
+    constexpr int kImg = kNT * LDR;       // elements of one row-major image
+    constexpr int kImgT = RP * LDT;       // elements of one transposed image
+    constexpr int kBuf = 2 * kImg + 2 * kImgT;   // hi, lo row-major; hi, lo transposed
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float* Vs = smem;                                             // [D][LDV]
+    uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);  // [2][kBuf]
+    const int b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i16 = lane & 15, g = lane >> 4;
+    const int len = user_len(lengths, b, N);
+    const int m_wave = blockIdx.x * (kWaves * kQB * 16) + wave * (kQB * 16);
+    const float* Pb = P + (size_t)b * N * r;
+
+    for (int e = tid; e < D * RP; e += kThreads) {
+        const int k = e / RP, c = e % RP;
+        Vs[k * LDV + c] = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
+    }
+    // zero both tile buffers once: padded rank columns / rows stay zero for ever
+    for (int e = tid; e < 2 * kBuf / 2; e += kThreads) reinterpret_cast<uint32_t*>(tiles)[e] = 0u;
+    __syncthreads();
+
+    // ---- prologue: Qt^T = V^T Q^T in float, scaled by scale*log2(e), split hi/lo ------
+    // accumulator (lane group g, register t) of block ib is rank 16*ib + 4*g + t
+    v4u qhi[kQB][RB2], qlo[kQB][RB2];
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) {
+        v4f qt[RB];
+#pragma unroll
+        for (int ib = 0; ib < RB; ++ib) qt[ib] = v4f{0.f, 0.f, 0.f, 0.f};
+        const int m = m_wave + 16 * qb + i16;
+        const bool valid = m < M;
+        const size_t row = ((size_t)b * M + (valid ? m : 0)) * D;
+        for (int kk = 0; kk < D / 16; ++kk) {
+            v4f q4;
+            if constexpr (BF16) {
+                uint2 w = reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(Qv) + row)[4 * kk + g];
+                q4 = v4f{bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y)};
+            } else {
+                q4 = reinterpret_cast<const v4f*>(reinterpret_cast<const float*>(Qv) + row)[4 * kk + g];
+            }
+            if (!valid) q4 = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float* vrow = Vs + (16 * kk + 4 * g + t) * LDV;
+#pragma unroll
+                for (int ib = 0; ib < RB; ++ib) qt[ib] = mfma16x16x4(vrow[16 * ib + i16], q4[t], qt[ib]);
+            }
+        }
+        // B operand of the score MFMA, chunk kk of 32 ranks: slot (g, u) is rank
+        // 32*kk + 16*(u/4) + 4*g + u%4, i.e. registers of blocks 2*kk and 2*kk+1
+#pragma unroll
+        for (int kk = 0; kk < RB2; ++kk) {
+            float h[8], l[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) split_bf16(qt[2 * kk + u / 4][u % 4] * (scale * kLog2e), h[u], l[u]);
+            qhi[qb][kk] = v4u{pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]), pack_bf16(h[4], h[5]), pack_bf16(h[6], h[7])};
+            qlo[qb][kk] = v4u{pack_bf16(l[0], l[1]), pack_bf16(l[2], l[3]), pack_bf16(l[4], l[5]), pack_bf16(l[6], l[7])};
+        }
+    }
+
+    v4f z[kQB][RB], lacc[kQB];
+    float mrun[kQB];
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) {
+        mrun[qb] = -INFINITY;
+        lacc[qb] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ib = 0; ib < RB; ++ib) z[qb][ib] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
+    const uint32_t one2 = 0x3f803f80u;   // two bf16 ones
+    const v4u ones = v4u{one2, one2, one2, one2};
+
+    // ---- tile loader: float P -> (hi, lo) bf16, row-major and transposed ---------------
+    const int quads_per_row = r >> 2;                      // r % 4 == 0 on this path
+    constexpr int kMaxLoads = (kNT * (RP / 4) + kThreads - 1) / kThreads;
+    v4f stage[kMaxLoads];
+    auto fetch = [&](int tile) {
+        const int n0 = tile * kNT;
+#pragma unroll
+        for (int i = 0; i < kMaxLoads; ++i) {
+            const int e = tid + i * kThreads;
+            const int nn = e / quads_per_row, c4 = e % quads_per_row;
+            stage[i] = v4f{0.f, 0.f, 0.f, 0.f};
+            if (nn < kNT && n0 + nn < len)
+                stage[i] = *reinterpret_cast<const v4f*>(Pb + (size_t)(n0 + nn) * r + 4 * c4);
+        }
+    };
+    auto commit = [&](uint16_t* buf) {
+        uint16_t* rhi = buf;
+        uint16_t* rlo = buf + kImg;
+        uint16_t* thi = buf + 2 * kImg;
+        uint16_t* tlo = thi + kImgT;
+#pragma unroll
+        for (int i = 0; i < kMaxLoads; ++i) {
+            const int e = tid + i * kThreads;
+            const int nn = e / quads_per_row, c4 = e % quads_per_row;
+            if (nn < kNT) {
+                float h[4], l[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) split_bf16(stage[i][c], h[c], l[c]);
+                const uint32_t h01 = pack_bf16(h[0], h[1]), h23 = pack_bf16(h[2], h[3]);
+                const uint32_t l01 = pack_bf16(l[0], l[1]), l23 = pack_bf16(l[2], l[3]);
+                *reinterpret_cast<uint2*>(rhi + nn * LDR + 4 * c4) = uint2{h01, h23};
+                *reinterpret_cast<uint2*>(rlo + nn * LDR + 4 * c4) = uint2{l01, l23};
+                thi[(4 * c4 + 0) * LDT + nn] = (uint16_t)(h01 & 0xffffu);
+                thi[(4 * c4 + 1) * LDT + nn] = (uint16_t)(h01 >> 16);
+                thi[(4 * c4 + 2) * LDT + nn] = (uint16_t)(h23 & 0xffffu);
+                thi[(4 * c4 + 3) * LDT + nn] = (uint16_t)(h23 >> 16);
+                tlo[(4 * c4 + 0) * LDT + nn] = (uint16_t)(l01 & 0xffffu);
+                tlo[(4 * c4 + 1) * LDT + nn] = (uint16_t)(l01 >> 16);
+                tlo[(4 * c4 + 2) * LDT + nn] = (uint16_t)(l23 & 0xffffu);
+                tlo[(4 * c4 + 3) * LDT + nn] = (uint16_t)(l23 >> 16);
+            }
+        }
+    };
+
+    const int ntiles = ceil_div(len, kNT);
+    if (ntiles > 0) { fetch(0); commit(tiles); }
+    __syncthreads();
+
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const uint16_t* buf = tiles + (tile & 1) * kBuf;
+        const uint16_t* rhi = buf;
+        const uint16_t* rlo = buf + kImg;
+        const uint16_t* thi = buf + 2 * kImg;
+        const uint16_t* tlo = thi + kImgT;
+        const bool more = tile + 1 < ntiles;
+        if (more) fetch(tile + 1);
+        const int n0 = tile * kNT;
+
+        // scores S^T[n][m]: A = 16 rows of P, slot (g, u) = rank 32*kk + 16*(u/4) + 4*g + u%4
+        v4f s[kQB][kNT / 16];
+#pragma unroll
+        for (int nb = 0; nb < kNT / 16; ++nb) {
+#pragma unroll
+            for (int qb = 0; qb < kQB; ++qb) s[qb][nb] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < RB2; ++kk) {
+                const int off = (16 * nb + i16) * LDR + 32 * kk + 4 * g;
+                const uint2 h0 = *reinterpret_cast<const uint2*>(rhi + off);
+                const uint2 h1 = *reinterpret_cast<const uint2*>(rhi + off + 16);
+                const uint2 l0 = *reinterpret_cast<const uint2*>(rlo + off);
+                const uint2 l1 = *reinterpret_cast<const uint2*>(rlo + off + 16);
+                const v4u ah = v4u{h0.x, h0.y, h1.x, h1.y};
+                const v4u al = v4u{l0.x, l0.y, l1.x, l1.y};
+#pragma unroll
+                for (int qb = 0; qb < kQB; ++qb) {
+                    s[qb][nb] = mfma16x16x32bf16(ah, qhi[qb][kk], s[qb][nb]);
+                    s[qb][nb] = mfma16x16x32bf16(al, qhi[qb][kk], s[qb][nb]);
+                    s[qb][nb] = mfma16x16x32bf16(ah, qlo[qb][kk], s[qb][nb]);
+                }
+            }
+        }
+        // mask rows past the valid length (register t of block nb is row 16*nb + 4*g + t)
+        if (n0 + kNT > len) {
+#pragma unroll
+            for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (n0 + 16 * nb + 4 * g + t >= len) {
+#pragma unroll
+                        for (int qb = 0; qb < kQB; ++qb) s[qb][nb][t] = -INFINITY;
+                    }
+        }
+        // online softmax per query (= lane column); weights rounded to bf16 and packed as
+        // the B operand of the next product: slot (g, u) of chunk kb is row
+        // 32*kb + 16*(u/4) + 4*g + u%4
+        v4u wp[kQB][kNT / 32];
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) {
+            float mt = -INFINITY;
+#pragma unroll
+            for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) mt = fmaxf(mt, s[qb][nb][t]);
+            mt = wave_xor_max(mt, 16);
+            mt = wave_xor_max(mt, 32);
+            const float mnew = fmaxf(mrun[qb], mt);   // finite: every tile has a valid row
+            const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - mnew);
+            mrun[qb] = mnew;
+#pragma unroll
+            for (int kb = 0; kb < kNT / 32; ++kb) {
+                float w[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) w[u] = __builtin_amdgcn_exp2f(s[qb][2 * kb + u / 4][u % 4] - mnew);
+                wp[qb][kb] = v4u{pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]),
+                                 pack_bf16(w[6], w[7])};
+            }
+            lacc[qb] *= alpha;
+#pragma unroll
+            for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= alpha;
+        }
+        // Z^T += P^T W^T and the row sums l += 1^T W^T
+#pragma unroll
+        for (int kb = 0; kb < kNT / 32; ++kb) {
+#pragma unroll
+            for (int qb = 0; qb < kQB; ++qb) lacc[qb] = mfma16x16x32bf16(ones, wp[qb][kb], lacc[qb]);
+#pragma unroll
+            for (int ib = 0; ib < RB; ++ib) {
+                const int off = (16 * ib + i16) * LDT + 32 * kb + 4 * g;
+                const uint2 h0 = *reinterpret_cast<const uint2*>(thi + off);
+                const uint2 h1 = *reinterpret_cast<const uint2*>(thi + off + 16);
+                const uint2 l0 = *reinterpret_cast<const uint2*>(tlo + off);
+                const uint2 l1 = *reinterpret_cast<const uint2*>(tlo + off + 16);
+                const v4u ah = v4u{h0.x, h0.y, h1.x, h1.y};
+                const v4u al = v4u{l0.x, l0.y, l1.x, l1.y};
+#pragma unroll
+                for (int qb = 0; qb < kQB; ++qb) {
+                    z[qb][ib] = mfma16x16x32bf16(ah, wp[qb][kb], z[qb][ib]);
+                    z[qb][ib] = mfma16x16x32bf16(al, wp[qb][kb], z[qb][ib]);
+                }
+            }
+        }
+        if (more) commit(tiles + ((tile + 1) & 1) * kBuf);
+        __syncthreads();
+    }
+
+    // ---- epilogue in float: O^T = V (Z / l)^T ------------------------------------------
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) {
+        const float l = lacc[qb][0];
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+#pragma unroll
+        for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= inv;
+        const int m = m_wave + 16 * qb + i16;
+        for (int cb = 0; cb < D / 16; ++cb) {
+            v4f o = v4f{0.f, 0.f, 0.f, 0.f};
+            const float* vrow = Vs + (16 * cb + i16) * LDV;
+#pragma unroll
+            for (int ib = 0; ib < RB; ++ib)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    o = mfma16x16x4(vrow[16 * ib + 4 * g + t], z[qb][ib][t], o);
+            if (m < M) *reinterpret_cast<v4f*>(O + ((size_t)b * M + m) * D + 16 * cb + 4 * g) = o;
+        }
+    }
+}
+
+template <int D, int RB2>
+hipError_t launch_t(const void* Q, const float* V, const float* P, const int32_t* lengths, int B,
+                    int N, int r, int M, float scale, bool bf16, float* O, hipStream_t stream) {
+    constexpr int RP = 32 * RB2;
+    const size_t lds = sizeof(float) * (size_t)D * (RP + 4) +
+                       sizeof(uint16_t) * 2 * (2 * (size_t)kNT * (RP + 8) + 2 * (size_t)RP * (kNT + 8));
+    dim3 grid(ceil_div(M, kWaves * kQB * 16), B), block(kThreads);
+    if (bf16) {
+        auto kern = attention_seq_bf16_kernel<D, RB2, true>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, N, r, M, scale, O);
+    } else {
+        auto kern = attention_seq_bf16_kernel<D, RB2, false>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, N, r, M, scale, O);
+    }
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_d(const void* Q, const float* V, const float* P, const int32_t* lengths, int B,
+                    int N, int r, int M, float scale, bool bf16, float* O, hipStream_t stream) {
+    if (r <= 32) return launch_t<D, 1>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+    if constexpr (D < 256) {
+        if (r <= 64) return launch_t<D, 2>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+bool attention_seq_bf16_supported(int d, int r) {
+    return (d == 64 || d == 128 || d == 256) && r >= 4 && r <= (d == 256 ? 32 : 64) && (r % 4) == 0;
+}
+
+hipError_t launch_attention_seq_bf16(const void* Q, const float* V, const float* P,
+                                     const int32_t* lengths, int B, int N, int d, int r, int M,
+                                     float scale, bool bf16, float* O, hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_d<64>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        case 128: return launch_d<128>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        case 256: return launch_d<256>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace solar

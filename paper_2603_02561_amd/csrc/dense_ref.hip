@@ -18,7 +18,7 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void dense_ref_kernel(
     const void* __restrict__ Qv, const void* __restrict__ Xv, const int32_t* __restrict__ lengths,
     int N, int d, int M, float scale, float* __restrict__ O) {
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const int LDX = d + 1;
     float* qs = smem;                 // [kDM][d]
     float* xs = qs + kDM * d;         // [kDN][LDX]

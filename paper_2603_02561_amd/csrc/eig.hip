@@ -14,6 +14,13 @@
 // deficiency (columns that vanish are dropped).  Power steps are repeated until
 // every wanted pair (theta_i, q_i) has residual |G q_i - theta_i q_i| below
 // tol_res * theta_max.
+//
+// The phase is bound by latency, not by throughput: a Jacobi sweep is L-1 rounds of
+// L/2 independent column rotations with a workgroup barrier after each round.  The
+// kernel therefore runs 16 waves (4 per SIMD) so that LDS latency of one wave hides
+// behind the others, gives every column pair a team of lanes whose partial dot
+// products are combined with DPP lane permutations, and keeps every trip count a
+// compile-time constant.
 #include "common.h"
 #include "kernels.h"
 
@@ -21,10 +28,28 @@ namespace solar {
 
 namespace {
 
-constexpr int kEigThreads = 256;
+#ifndef SOLAR_EIG_THREADS
+#define SOLAR_EIG_THREADS 512
+#endif
+#ifndef SOLAR_EIG_TMAX
+#define SOLAR_EIG_TMAX 16
+#endif
+constexpr int kEigThreads = SOLAR_EIG_THREADS;
+constexpr int kEigWaves = kEigThreads / 64;
 // A column of the iterate whose norm falls below this fraction of the largest column norm
 // is rounding noise of the float Gram matrix (about sqrt(d) * 2^-24 relative) and is dropped.
 constexpr float kDeadRel = 1.0e-5f;
+// Rotations are skipped below this |cos|; a sweep that meets no |cos| above kSweepDone
+// leaves every |cos| below about L * kSweepDone^2 (quadratic convergence) and ends the phase.
+constexpr float kSkipCos = 1.0e-7f;
+constexpr float kSweepDone = 2.0e-4f;
+
+__host__ __device__ constexpr int pow2floor_c(int x) {
+    int p = 1;
+    while (2 * p <= x) p *= 2;
+    return p;
+}
+__host__ __device__ constexpr int min_c(int a, int b) { return a < b ? a : b; }
 
 __device__ __forceinline__ uint32_t mix32(uint32_t x) {
     x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
@@ -40,139 +65,132 @@ __device__ __forceinline__ float omega_entry(int b, int j, int i) {
     return sqrtf(-2.0f * __logf(u1)) * __cosf(6.28318530718f * u2);
 }
 
-__device__ __forceinline__ int pow2floor(int x) {
-    int p = 1;
-    while (2 * p <= x) p *= 2;
-    return p;
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
 
-// Z = G Q with the float 16x16x4 MFMA.  G is symmetric, so A[i][k] = G[k][i] is read
-// with the 16 lanes of a slot group on consecutive addresses.  Q and Z are stored
-// column by column (column j at base + j*LD).
-template <int D, int CB>
-__device__ __forceinline__ void gemm_gq(const float* __restrict__ Gb, const float* Qc, float* Zc,
-                                        int LD) {
-    constexpr int RB = (D / 16 + 3) / 4;
+// Sum over a team of T consecutive lanes (T a power of two, team aligned to T); every
+// lane of the team receives the same bits.  Up to 16 lanes the exchange is a DPP operand
+// (quad permutes, then mirror within 8 and within 16 lanes).
+template <int T>
+__device__ __forceinline__ float team_sum(float v) {
+    if constexpr (T >= 2) v += dpp_mov<0xB1>(v);    // quad_perm [1,0,3,2]
+    if constexpr (T >= 4) v += dpp_mov<0x4E>(v);    // quad_perm [2,3,0,1]
+    if constexpr (T >= 8) v += dpp_mov<0x141>(v);   // row_half_mirror
+    if constexpr (T >= 16) v += dpp_mov<0x140>(v);  // row_mirror
+    if constexpr (T >= 32) v += __shfl_xor(v, 16);
+    if constexpr (T >= 64) v += __shfl_xor(v, 32);
+    return v;
+}
+
+// Z = G Q with the float 16x16x4 MFMA, 16x16 output blocks dealt round-robin to the
+// waves.  G is symmetric, so A[i][k] = G[k][i] is read with the 16 lanes of a slot group
+// on consecutive addresses.  Q and Z are stored column by column (column j at j*LD).
+template <int D, int LP>
+__device__ __forceinline__ void gemm_gq(const float* __restrict__ Gb, const float* Qc, float* Zc) {
+    constexpr int LD = D + 4;
+    constexpr int NRB = D / 16, NB = NRB * (LP / 16);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i16 = lane & 15, g = lane >> 4;
-    v4f acc[RB][CB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) acc[rb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int k0 = 0; k0 < D; k0 += 4) {
-        float a[RB];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            const int ib = wave + 4 * rb;
-            a[rb] = (16 * ib < D) ? Gb[(size_t)(k0 + g) * D + 16 * ib + i16] : 0.f;
-        }
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            const float q = Qc[(16 * cb + i16) * LD + k0 + g];
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) acc[rb][cb] = mfma16x16x4(a[rb], q, acc[rb][cb]);
-        }
-    }
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int ib = wave + 4 * rb;
-        if (16 * ib < D) {
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-                *reinterpret_cast<v4f*>(&Zc[(16 * cb + i16) * LD + 16 * ib + 4 * g]) = acc[rb][cb];
-        }
+    for (int blk = wave; blk < NB; blk += kEigWaves) {
+        const int ib = blk % NRB, cb = blk / NRB;
+        const float* ga = Gb + (size_t)g * D + 16 * ib + i16;
+        const float* qb = Qc + (16 * cb + i16) * LD + g;
+        v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 16
+        for (int k0 = 0; k0 < D; k0 += 4) acc = mfma16x16x4(ga[(size_t)k0 * D], qb[k0], acc);
+        *reinterpret_cast<v4f*>(&Zc[(16 * cb + i16) * LD + 16 * ib + 4 * g]) = acc;
     }
 }
 
-// One cyclic sweep of one-sided Jacobi over the first L columns of Zc (L even):
-// L-1 rounds of L/2 disjoint column pairs (round-robin tournament), one team of T
-// lanes per pair.  Returns the largest |cos| between two columns met in the sweep.
-template <int D>
-__device__ float jacobi_sweep(float* Zc, int L, int LD, int T, float skip_tol, int* sh_bits,
-                              int* sh_amax) {
-    constexpr int CHMAX = 8;
+template <int D, int L>
+struct EigCfg {
+    static constexpr int LP = 16 * ((L + 15) / 16);
+    static constexpr int LD = D + 4;
+    static constexpr int NPAIR = L / 2;
+    // lanes per column pair in a Jacobi round, lanes per column elsewhere
+    // (at most 16, so that a team's sums are pure DPP exchanges)
+    static constexpr int TJ = min_c(min_c(SOLAR_EIG_TMAX, D / 4), pow2floor_c(kEigThreads / NPAIR));
+    static constexpr int CH = D / (4 * TJ);
+    static constexpr int TC = min_c(min_c(64, D), pow2floor_c(kEigThreads / L));
+    static constexpr size_t lds_floats = (size_t)2 * LP * LD + 3 * LP + 8;
+};
+
+// One cyclic sweep of one-sided Jacobi over the L columns of Zc: L-1 rounds of L/2
+// disjoint column pairs (round-robin tournament), one team of TJ lanes per pair.  Returns this thread's largest |cos| met in the sweep.
+template <int D, int L>
+__device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
+    using C = EigCfg<D, L>;
+    constexpr int T = C::TJ, CH = C::CH, LD = C::LD, NPAIR = C::NPAIR;
     const int tid = threadIdx.x;
     const int team = tid / T, u = tid % T;
-    const int npair = L / 2;
-    const int CH = D / (4 * T);
     float offmax = 0.f;
+#pragma unroll 1
     for (int rho = 0; rho < L - 1; ++rho) {
-        if (team < npair) {
-            int p, q;
-            if (team == 0) { p = L - 1; q = rho; }
-            else { p = (rho + team) % (L - 1); q = (rho - team + (L - 1)) % (L - 1); }
-            if (p > q) { int t = p; p = q; q = t; }
-            float* zp = Zc + p * LD;
-            float* zq = Zc + q * LD;
-            v4f a[CHMAX], c[CHMAX];
+        if (team < NPAIR) {
+            // round-robin tournament: pair 0 is (L-1, rho), pair k is
+            // ((rho+k) mod (L-1), (rho-k) mod (L-1))
+            int p = rho + team, q = rho - team;
+            if (p >= L - 1) p -= L - 1;
+            if (q < 0) q += L - 1;
+            if (team == 0) p = L - 1;
+            float* zp = Zc + p * LD + 4 * u;
+            float* zq = Zc + q * LD + 4 * u;
+            v4f a[CH], c[CH];
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                a[k] = *reinterpret_cast<const v4f*>(zp + 4 * T * k);
+                c[k] = *reinterpret_cast<const v4f*>(zq + 4 * T * k);
+            }
             float al = 0.f, be = 0.f, ga = 0.f;
 #pragma unroll
-            for (int k = 0; k < CHMAX; ++k)
-                if (k < CH) {
-                    a[k] = *reinterpret_cast<const v4f*>(zp + 4 * (u + T * k));
-                    c[k] = *reinterpret_cast<const v4f*>(zq + 4 * (u + T * k));
-                    al += a[k].x * a[k].x + a[k].y * a[k].y + a[k].z * a[k].z + a[k].w * a[k].w;
-                    be += c[k].x * c[k].x + c[k].y * c[k].y + c[k].z * c[k].z + c[k].w * c[k].w;
-                    ga += a[k].x * c[k].x + a[k].y * c[k].y + a[k].z * c[k].z + a[k].w * c[k].w;
-                }
-            for (int m = 1; m < T; m <<= 1) {
-                al += __shfl_xor(al, m);
-                be += __shfl_xor(be, m);
-                ga += __shfl_xor(ga, m);
+            for (int k = 0; k < CH; ++k) {
+                al += a[k].x * a[k].x + a[k].y * a[k].y + a[k].z * a[k].z + a[k].w * a[k].w;
+                be += c[k].x * c[k].x + c[k].y * c[k].y + c[k].z * c[k].z + c[k].w * c[k].w;
+                ga += a[k].x * c[k].x + a[k].y * c[k].y + a[k].z * c[k].z + a[k].w * c[k].w;
             }
-            // Columns that have collapsed to rounding noise (squared norm below kDeadRel^2 of
-            // the largest seen) are left alone: they are dropped at normalization.
-            // (read once per team so that every lane of the team takes the same branch)
-            const float amax = __shfl(__int_as_float(*sh_amax), (tid & 63) - u);
-            if (u == 0 && fmaxf(al, be) > amax) atomicMax(sh_amax, __float_as_int(fmaxf(al, be)));
-            const float dead = kDeadRel * kDeadRel * fmaxf(amax, fmaxf(al, be));
-            const float den = sqrtf(al) * sqrtf(be);
-            if (den > 0.f && al > dead && be > dead) {
-                const float cosv = fabsf(ga) / den;
+            al = team_sum<T>(al);
+            be = team_sum<T>(be);
+            ga = team_sum<T>(ga);
+            // columns that have collapsed to rounding noise are left alone (dropped later)
+            if (al > dead2 && be > dead2) {
+                const float cosv = fabsf(ga) * __builtin_amdgcn_rsqf(al) * __builtin_amdgcn_rsqf(be);
                 offmax = fmaxf(offmax, cosv);
-                if (cosv > skip_tol) {
-                    const float zeta = (be - al) / (2.f * ga);
-                    const float t = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
-                    const float cs = 1.f / sqrtf(1.f + t * t);
+                if (cosv > kSkipCos) {
+                    const float zeta = 0.5f * (be - al) * __builtin_amdgcn_rcpf(ga);
+                    const float t = copysignf(1.f, zeta) *
+                                    __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+                    const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
                     const float sn = cs * t;
 #pragma unroll
-                    for (int k = 0; k < CHMAX; ++k)
-                        if (k < CH) {
-                            const v4f x = a[k], y = c[k];
-                            *reinterpret_cast<v4f*>(zp + 4 * (u + T * k)) = cs * x - sn * y;
-                            *reinterpret_cast<v4f*>(zq + 4 * (u + T * k)) = sn * x + cs * y;
-                        }
+                    for (int k = 0; k < CH; ++k) {
+                        const v4f x = a[k], y = c[k];
+                        *reinterpret_cast<v4f*>(zp + 4 * T * k) = cs * x - sn * y;
+                        *reinterpret_cast<v4f*>(zq + 4 * T * k) = sn * x + cs * y;
+                    }
                 }
             }
         }
         __syncthreads();
     }
-    atomicMax(sh_bits, __float_as_int(offmax));
-    __syncthreads();
-    const float result = __int_as_float(*sh_bits);
-    __syncthreads();
-    if (tid == 0) *sh_bits = 0;
-    __syncthreads();
-    return result;
+    return offmax;
 }
 
-template <int D, int CB>
+template <int D, int L>
 __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
-    const float* __restrict__ G, const int32_t* __restrict__ lengths, int N, int r, int L,
+    const float* __restrict__ G, const int32_t* __restrict__ lengths, int N, int r,
     float* __restrict__ S, float* __restrict__ V, int32_t* __restrict__ info, EigParams prm) {
-    constexpr int LP = 16 * CB;
-    constexpr int LD = D + 4;
-    extern __shared__ float smem[];
+    using C = EigCfg<D, L>;
+    constexpr int LP = C::LP, LD = C::LD, TC = C::TC;
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Zc = smem;
     float* Qc = Zc + LP * LD;
     float* theta = Qc + LP * LD;   // [LP]
     float* resid = theta + LP;     // [LP] residuals, also column norms
-    int* rankv = reinterpret_cast<int*>(resid + LP);  // [LP]
+    int* rankv = reinterpret_cast<int*>(resid + LP);              // [LP]
     __shared__ int sh_bits;
     __shared__ int sh_bits2;
-    __shared__ int sh_amax;
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const float* Gb = G + (size_t)b * D * D;
@@ -186,8 +204,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
             return;
         }
     }
-    if (tid == 0) { sh_bits = 0; sh_bits2 = 0; sh_amax = 0; }
-
+    if (tid == 0) { sh_bits = 0; sh_bits2 = 0; }
     // start block Omega (columns >= L stay zero so that the padded GEMM columns are zero)
     for (int e = tid; e < LP * D; e += kEigThreads) {
         const int j = e / D, i = e % D;
@@ -196,30 +213,40 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     }
     __syncthreads();
 
-    const int TJ = min(min(64, D / 4), pow2floor(kEigThreads / (L / 2)));  // lanes per column pair
-    const int TC = min(64, pow2floor(kEigThreads / L));                    // lanes per column
     const int col = tid / TC, cu = tid % TC;
     bool orth_ok = false;
     float prev_res = 3.0e38f;
     int it = 0;
     int status = 0;
+    int total_sweeps = 0;
+    long long cyc_gemm = 0, cyc_jac = 0;
+    const long long wall0 = wall_clock64();
+    const long long cyc0 = clock64();
     for (;; ++it) {
-        gemm_gq<D, CB>(Gb, Qc, Zc, LD);
+        long long t0 = clock64();
+        gemm_gq<D, LP>(Gb, Qc, Zc);
         __syncthreads();
-        if (it > 0) {
-            // Rayleigh quotients and residuals of the current basis
-            if (col < L) {
-                const float* q = Qc + col * LD;
-                const float* z = Zc + col * LD;
-                float th = 0.f;
-                for (int i = cu; i < D; i += TC) th += q[i] * z[i];
-                for (int m = 1; m < TC; m <<= 1) th += __shfl_xor(th, m);
-                float rs = 0.f;
-                for (int i = cu; i < D; i += TC) { const float e = z[i] - th * q[i]; rs += e * e; }
-                for (int m = 1; m < TC; m <<= 1) rs += __shfl_xor(rs, m);
-                if (cu == 0) { theta[col] = th; resid[col] = sqrtf(rs); }
+        cyc_gemm += clock64() - t0;
+        // column norms of Z (for the dead-column threshold), Rayleigh quotients and residuals
+        if (col < L) {
+            const float* q = Qc + col * LD;
+            const float* z = Zc + col * LD;
+            float th = 0.f, nn = 0.f;
+            for (int i = cu; i < D; i += TC) { th += q[i] * z[i]; nn += z[i] * z[i]; }
+            th = team_sum<TC>(th);
+            nn = team_sum<TC>(nn);
+            float rs = 0.f;
+            for (int i = cu; i < D; i += TC) { const float e = z[i] - th * q[i]; rs += e * e; }
+            rs = team_sum<TC>(rs);
+            if (cu == 0) {
+                theta[col] = th;
+                resid[col] = sqrtf(rs);
+                atomicMax(&sh_bits2, __float_as_int(nn));
             }
-            __syncthreads();
+        }
+        __syncthreads();
+        const float dead2 = kDeadRel * kDeadRel * __int_as_float(sh_bits2);
+        if (it > 0) {
             if (tid < L) {
                 const float th = theta[tid];
                 int rk = 0;
@@ -229,14 +256,11 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
                 }
                 rankv[tid] = rk;
                 if (rk < r) atomicMax(&sh_bits, __float_as_int(resid[tid]));
-                if (rk == 0) sh_bits2 = __float_as_int(fmaxf(th, 0.f));
             }
             __syncthreads();
             const float maxres = __int_as_float(sh_bits);
-            const float thmax = __int_as_float(sh_bits2);
-            __syncthreads();
-            if (tid == 0) sh_bits = 0;
-            __syncthreads();
+            float thmax = 0.f;
+            for (int k = 0; k < L; ++k) thmax = fmaxf(thmax, theta[k]);
             bool done = orth_ok && (maxres <= prm.tol_res * thmax);
             // stagnation at the rounding floor counts as converged
             if (orth_ok && it >= 3 && maxres > 0.5f * prev_res && maxres <= 1.0e-4f * thmax) done = true;
@@ -244,20 +268,24 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
             if (done) break;
             if (it >= prm.max_iter) { status = it; break; }
         }
+        __syncthreads();
+        if (tid == 0) { sh_bits = 0; sh_bits2 = 0; }
         // orthogonalize the columns of Z (this also rotates them towards Ritz vectors)
         orth_ok = false;
-        if (tid == 0) sh_amax = 0;
-        __syncthreads();
+        t0 = clock64();
         for (int sw = 0; sw < prm.sweeps; ++sw) {
-            const float off = jacobi_sweep<D>(Zc, L, LD, TJ, 1.0e-7f, &sh_bits, &sh_amax);
-            if (off <= prm.tol_orth) { orth_ok = true; break; }
+            const float mine = jacobi_sweep<D, L>(Zc, dead2);
+            ++total_sweeps;
+            const bool any = __syncthreads_or(mine > kSweepDone);
+            if (!any) { orth_ok = true; break; }
         }
+        cyc_jac += clock64() - t0;
         // normalize; drop columns that are numerically zero
         if (col < L) {
             const float* z = Zc + col * LD;
             float nn = 0.f;
             for (int i = cu; i < D; i += TC) nn += z[i] * z[i];
-            for (int m = 1; m < TC; m <<= 1) nn += __shfl_xor(nn, m);
+            nn = team_sum<TC>(nn);
             if (cu == 0) resid[col] = sqrtf(nn);
         }
         __syncthreads();
@@ -292,7 +320,52 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
         for (int i = cu; i < D; i += TC) V[((size_t)b * D + i) * r + k] = sgn * q[i];
         if (cu == 0) S[(size_t)b * r + k] = sqrtf(fmaxf(theta[col], 0.f));
     }
-    if (tid == 0 && info) info[b] = status;
+    if (tid == 0 && info) {
+        int v = status;
+        if (prm.debug_counts == 1) v = it * 1000 + total_sweeps;
+        if (prm.debug_counts == 2) v = (int)(cyc_jac / (total_sweeps * (L - 1)));   // cycles per round
+        if (prm.debug_counts == 3) v = (int)(cyc_gemm / (it + 1));                   // cycles per GEMM
+        if (prm.debug_counts == 4) v = (int)(wall_clock64() - wall0);                // 100 MHz ticks
+        if (prm.debug_counts == 5) v = (int)((clock64() - cyc0) / 1000);             // kilo-cycles
+        info[b] = v;
+    }
+}
+
+template <int D, int L>
+hipError_t launch_eig_t(const float* G, const int32_t* lengths, int B, int N, int r, float* S,
+                        float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
+    const size_t lds = sizeof(float) * EigCfg<D, L>::lds_floats;
+    auto kern = eig_topr_kernel<D, L>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(B), dim3(kEigThreads), lds, stream, G, lengths, N, r, S, V, info,
+                       prm);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_eig_d(const float* G, const int32_t* lengths, int B, int N, int r, float* S,
+                        float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
+    const int L = eig_block_columns(D, r);
+#define SOLAR_EIG_CASE(LL)                                                                    \
+    case LL:                                                                                  \
+        if constexpr (LL <= D && (D < 256 || LL <= 40))                                       \
+            return launch_eig_t<D, LL>(G, lengths, B, N, r, S, V, info, prm, stream);         \
+        else                                                                                  \
+            return hipErrorInvalidValue;
+    switch (L) {
+        SOLAR_EIG_CASE(16)
+        SOLAR_EIG_CASE(24)
+        SOLAR_EIG_CASE(32)
+        SOLAR_EIG_CASE(40)
+        SOLAR_EIG_CASE(48)
+        SOLAR_EIG_CASE(56)
+        SOLAR_EIG_CASE(64)
+        SOLAR_EIG_CASE(72)
+        default: return hipErrorInvalidValue;
+    }
+#undef SOLAR_EIG_CASE
 }
 
 }  // namespace
@@ -303,11 +376,14 @@ EigParams eig_default_params() {
     p.tol_orth = 2.0e-6f;
     p.max_iter = 40;
     p.sweeps = 12;
+    p.debug_counts = 0;
     return p;
 }
 
+// Columns of the iterate block: r plus an oversampling of 8, rounded up to a multiple of 8.
 int eig_block_columns(int d, int r) {
     int L = 8 * ((r + 8 + 7) / 8);
+    if (L < 16) L = 16;
     if (L > d) L = d;
     return L;
 }
@@ -315,42 +391,11 @@ int eig_block_columns(int d, int r) {
 size_t eig_lds_bytes(int d, int r) {
     const int L = eig_block_columns(d, r);
     const int LP = 16 * ((L + 15) / 16);
-    return sizeof(float) * ((size_t)2 * LP * (d + 4) + 3 * LP);
-}
-
-template <int D, int CB>
-static hipError_t launch_eig_t(const float* G, const int32_t* lengths, int B, int N, int r, int L,
-                               float* S, float* V, int32_t* info, const EigParams& prm,
-                               hipStream_t stream) {
-    const size_t lds = sizeof(float) * ((size_t)2 * 16 * CB * (D + 4) + 3 * 16 * CB);
-    auto kern = eig_topr_kernel<D, CB>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(B), dim3(kEigThreads), lds, stream, G, lengths, N, r, L, S, V,
-                       info, prm);
-    return hipGetLastError();
-}
-
-template <int D>
-static hipError_t launch_eig_d(const float* G, const int32_t* lengths, int B, int N, int r,
-                               float* S, float* V, int32_t* info, const EigParams& prm,
-                               hipStream_t stream) {
-    const int L = eig_block_columns(D, r);
-    const int CB = (L + 15) / 16;
-    switch (CB) {
-        case 1: return launch_eig_t<D, 1>(G, lengths, B, N, r, L, S, V, info, prm, stream);
-        case 2: return launch_eig_t<D, 2>(G, lengths, B, N, r, L, S, V, info, prm, stream);
-        case 3: return launch_eig_t<D, 3>(G, lengths, B, N, r, L, S, V, info, prm, stream);
-        case 4: return launch_eig_t<D, 4>(G, lengths, B, N, r, L, S, V, info, prm, stream);
-        case 5: return launch_eig_t<D, 5>(G, lengths, B, N, r, L, S, V, info, prm, stream);
-        default: return hipErrorInvalidValue;
-    }
+    return sizeof(float) * ((size_t)2 * LP * (d + 4) + 3 * LP + ((L - 1) * (L / 2) + 1) / 2 + 8);
 }
 
 hipError_t launch_eig(const float* G, const int32_t* lengths, int B, int N, int d, int r, float* S,
                       float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
-    if (eig_lds_bytes(d, r) > 160 * 1024) return hipErrorInvalidValue;
     switch (d) {
         case 64: return launch_eig_d<64>(G, lengths, B, N, r, S, V, info, prm, stream);
         case 128: return launch_eig_d<128>(G, lengths, B, N, r, S, V, info, prm, stream);

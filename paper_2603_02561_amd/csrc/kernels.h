@@ -19,6 +19,7 @@ struct EigParams {
     float tol_orth;     // a sweep whose largest |cos| is below this ends the Jacobi phase
     int max_iter;       // cap on power steps
     int sweeps;         // cap on Jacobi sweeps per power step
+    int debug_counts;   // nonzero: info[] returns 1000*power_steps + sweeps instead of status
 };
 EigParams eig_default_params();
 int eig_block_columns(int d, int r);
@@ -38,6 +39,12 @@ hipError_t launch_attention_seq(const void* Q, const float* V, const float* P,
 hipError_t launch_attention_tokens(const void* Q, const float* S, const float* V, int B, int d,
                                    int r, int M, float scale, bool softmax, bool bf16, float* O,
                                    hipStream_t stream);
+
+// attention_bf16.hip
+bool attention_seq_bf16_supported(int d, int r);
+hipError_t launch_attention_seq_bf16(const void* Q, const float* V, const float* P,
+                                     const int32_t* lengths, int B, int N, int d, int r, int M,
+                                     float scale, bool bf16, float* O, hipStream_t stream);
 
 // dense_ref.hip
 hipError_t launch_dense_ref(const void* Q, const void* X, const int32_t* lengths, int B, int N,

@@ -21,7 +21,7 @@ template <int D, bool BF16>
 __global__ __launch_bounds__(kProjThreads) void project_kernel(
     const void* __restrict__ Xv, const int32_t* __restrict__ lengths, const float* __restrict__ V,
     int N, int r, int RP, float* __restrict__ P) {
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     const int LDV = RP + 4;
     float* Vs = smem;  // [D][LDV], columns >= r are zero
     const int b = blockIdx.y;
