@@ -20,8 +20,9 @@
 // splits the tile: row-major (contraction over the rank index, for the scores) and
 // transposed (contraction over the sequence index, for Z).
 //
-// The kernel is bound by the vector ALU: per score one max, one subtract, one exp2
-// (transcendental rate) and half a pack instruction, against 5/16 of a 16-cycle MFMA.
+// The kernel is bound by the vector ALU: per score half a max3, one exp2 (transcendental
+// rate) and half a pack instruction, against 5/16 of a 16-cycle MFMA.  The subtraction of
+// the row maximum is folded into the accumulator start value of the score MFMA.
 // Eight waves per workgroup (two per SIMD) let the matrix unit of one wave run
 // under the exponentials of the other.
 #include "common.h"
@@ -31,11 +32,18 @@ namespace solar {
 
 namespace {
 
-constexpr int kThreads = 512;
+#ifndef SOLAR_ATTN_THREADS
+#define SOLAR_ATTN_THREADS 512
+#endif
+#ifndef SOLAR_ATTN_NT
+#define SOLAR_ATTN_NT 64
+#endif
+constexpr int kThreads = SOLAR_ATTN_THREADS;
 constexpr int kWaves = kThreads / 64;
 constexpr int kQB = 2;    // 16-query blocks per wave
-constexpr int kNT = 64;   // rows of P per tile
+constexpr int kNT = SOLAR_ATTN_NT;   // rows of P per tile
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kJump = 16.f;   // log2 units a tile maximum may exceed the reference by
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     // round to nearest even; inputs are finite
@@ -56,8 +64,11 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     constexpr int RP = 32 * RB2;          // padded rank
     constexpr int RB = RP / 16;
     constexpr int LDV = RP + 4;           // floats
-    constexpr int LDR = RP + 8;           // bf16 elements, row-major image  [kNT][LDR]
-    constexpr int LDT = kNT + 8;          // bf16 elements, transposed image [RP][LDT]
+#ifndef SOLAR_ATTN_RPAD
+#define SOLAR_ATTN_RPAD 4
+#endif
+    constexpr int LDR = RP + SOLAR_ATTN_RPAD;   // bf16 elements, row-major image  [kNT][LDR]
+    constexpr int LDT = kNT + 12;         // bf16 elements, transposed image [RP][LDT]
     constexpr int kImg = kNT * LDR;       // elements of one row-major image
     constexpr int kImgT = RP * LDT;       // elements of one transposed image
     constexpr int kBuf = 2 * kImg + 2 * kImgT;   // hi, lo row-major; hi, lo transposed
@@ -119,10 +130,10 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     }
 
     v4f z[kQB][RB], lacc[kQB];
-    float mrun[kQB];
+    float mref[kQB];
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb) {
-        mrun[qb] = -INFINITY;
+        mref[qb] = -INFINITY;
         lacc[qb] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ib = 0; ib < RB; ++ib) z[qb][ib] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -131,21 +142,27 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     const v4u ones = v4u{one2, one2, one2, one2};
 
     // ---- tile loader: float P -> (hi, lo) bf16, row-major and transposed ---------------
+    // A thread owns two consecutive rows and four consecutive ranks, so that the transposed
+    // image is written as 32-bit words (two rows of one rank).
     const int quads_per_row = r >> 2;                      // r % 4 == 0 on this path
-    constexpr int kMaxLoads = (kNT * (RP / 4) + kThreads - 1) / kThreads;
-    v4f stage[kMaxLoads];
-    auto fetch = [&](int tile) {
+    constexpr int kMaxLoads = ((kNT / 2) * (RP / 4) + kThreads - 1) / kThreads;
+    v4f stage[kMaxLoads][2];
+    auto fetch = [&](int tile) __attribute__((always_inline)) {
         const int n0 = tile * kNT;
 #pragma unroll
         for (int i = 0; i < kMaxLoads; ++i) {
             const int e = tid + i * kThreads;
-            const int nn = e / quads_per_row, c4 = e % quads_per_row;
-            stage[i] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (nn < kNT && n0 + nn < len)
-                stage[i] = *reinterpret_cast<const v4f*>(Pb + (size_t)(n0 + nn) * r + 4 * c4);
+            const int np = e / quads_per_row, c4 = e % quads_per_row;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int n = n0 + 2 * np + h;
+                stage[i][h] = v4f{0.f, 0.f, 0.f, 0.f};
+                if (np < kNT / 2 && n < len)
+                    stage[i][h] = *reinterpret_cast<const v4f*>(Pb + (size_t)n * r + 4 * c4);
+            }
         }
     };
-    auto commit = [&](uint16_t* buf) {
+    auto commit = [&](uint16_t* buf) __attribute__((always_inline)) {
         uint16_t* rhi = buf;
         uint16_t* rlo = buf + kImg;
         uint16_t* thi = buf + 2 * kImg;
@@ -153,23 +170,26 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
 #pragma unroll
         for (int i = 0; i < kMaxLoads; ++i) {
             const int e = tid + i * kThreads;
-            const int nn = e / quads_per_row, c4 = e % quads_per_row;
-            if (nn < kNT) {
-                float h[4], l[4];
+            const int np = e / quads_per_row, c4 = e % quads_per_row;
+            if (np < kNT / 2) {
+                float h[2][4], l[2][4];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) split_bf16(stage[i][c], h[c], l[c]);
-                const uint32_t h01 = pack_bf16(h[0], h[1]), h23 = pack_bf16(h[2], h[3]);
-                const uint32_t l01 = pack_bf16(l[0], l[1]), l23 = pack_bf16(l[2], l[3]);
-                *reinterpret_cast<uint2*>(rhi + nn * LDR + 4 * c4) = uint2{h01, h23};
-                *reinterpret_cast<uint2*>(rlo + nn * LDR + 4 * c4) = uint2{l01, l23};
-                thi[(4 * c4 + 0) * LDT + nn] = (uint16_t)(h01 & 0xffffu);
-                thi[(4 * c4 + 1) * LDT + nn] = (uint16_t)(h01 >> 16);
-                thi[(4 * c4 + 2) * LDT + nn] = (uint16_t)(h23 & 0xffffu);
-                thi[(4 * c4 + 3) * LDT + nn] = (uint16_t)(h23 >> 16);
-                tlo[(4 * c4 + 0) * LDT + nn] = (uint16_t)(l01 & 0xffffu);
-                tlo[(4 * c4 + 1) * LDT + nn] = (uint16_t)(l01 >> 16);
-                tlo[(4 * c4 + 2) * LDT + nn] = (uint16_t)(l23 & 0xffffu);
-                tlo[(4 * c4 + 3) * LDT + nn] = (uint16_t)(l23 >> 16);
+                for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) split_bf16(stage[i][hh][c], h[hh][c], l[hh][c]);
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const int nn = 2 * np + hh;
+                    *reinterpret_cast<uint2*>(rhi + nn * LDR + 4 * c4) =
+                        uint2{pack_bf16(h[hh][0], h[hh][1]), pack_bf16(h[hh][2], h[hh][3])};
+                    *reinterpret_cast<uint2*>(rlo + nn * LDR + 4 * c4) =
+                        uint2{pack_bf16(l[hh][0], l[hh][1]), pack_bf16(l[hh][2], l[hh][3])};
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    *reinterpret_cast<uint32_t*>(thi + (4 * c4 + c) * LDT + 2 * np) = pack_bf16(h[0][c], h[1][c]);
+                    *reinterpret_cast<uint32_t*>(tlo + (4 * c4 + c) * LDT + 2 * np) = pack_bf16(l[0][c], l[1][c]);
+                }
             }
         }
     };
@@ -188,12 +208,15 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         if (more) fetch(tile + 1);
         const int n0 = tile * kNT;
 
-        // scores S^T[n][m]: A = 16 rows of P, slot (g, u) = rank 32*kk + 16*(u/4) + 4*g + u%4
-        v4f s[kQB][kNT / 16];
+        // The work of a tile is staged so that the matrix unit and the vector ALU of the
+        // wave run side by side on different query blocks:
+        //   S(0) | S(1) + exp(0) | Z(0) + exp(1) | Z(1) + split of the next tile
+        // S(q): scores of query block q relative to its reference value: the accumulators
+        //       start at -mref (first tile: 0), so what leaves the matrix unit is s - mref.
+        //       A = 16 rows of P, slot (g, u) = rank 32*kk + 16*(u/4) + 4*g + u%4.
+        v4u sah[kNT / 16][RB2], sal[kNT / 16][RB2];
 #pragma unroll
-        for (int nb = 0; nb < kNT / 16; ++nb) {
-#pragma unroll
-            for (int qb = 0; qb < kQB; ++qb) s[qb][nb] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int nb = 0; nb < kNT / 16; ++nb)
 #pragma unroll
             for (int kk = 0; kk < RB2; ++kk) {
                 const int off = (16 * nb + i16) * LDR + 32 * kk + 4 * g;
@@ -201,76 +224,120 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                 const uint2 h1 = *reinterpret_cast<const uint2*>(rhi + off + 16);
                 const uint2 l0 = *reinterpret_cast<const uint2*>(rlo + off);
                 const uint2 l1 = *reinterpret_cast<const uint2*>(rlo + off + 16);
-                const v4u ah = v4u{h0.x, h0.y, h1.x, h1.y};
-                const v4u al = v4u{l0.x, l0.y, l1.x, l1.y};
-#pragma unroll
-                for (int qb = 0; qb < kQB; ++qb) {
-                    s[qb][nb] = mfma16x16x32bf16(ah, qhi[qb][kk], s[qb][nb]);
-                    s[qb][nb] = mfma16x16x32bf16(al, qhi[qb][kk], s[qb][nb]);
-                    s[qb][nb] = mfma16x16x32bf16(ah, qlo[qb][kk], s[qb][nb]);
-                }
+                sah[nb][kk] = v4u{h0.x, h0.y, h1.x, h1.y};
+                sal[nb][kk] = v4u{l0.x, l0.y, l1.x, l1.y};
             }
-        }
-        // mask rows past the valid length (register t of block nb is row 16*nb + 4*g + t)
-        if (n0 + kNT > len) {
+        v4f s[kQB][kNT / 16];
+        auto scores = [&](int qb) __attribute__((always_inline)) {
+            const float c0 = (mref[qb] == -INFINITY) ? 0.f : -mref[qb];
+            const v4f cinit = v4f{c0, c0, c0, c0};
 #pragma unroll
             for (int nb = 0; nb < kNT / 16; ++nb)
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (n0 + 16 * nb + 4 * g + t >= len) {
+                for (int kk = 0; kk < RB2; ++kk) {
+                    s[qb][nb] = mfma16x16x32bf16(sah[nb][kk], qhi[qb][kk], kk == 0 ? cinit : s[qb][nb]);
+                    s[qb][nb] = mfma16x16x32bf16(sal[nb][kk], qhi[qb][kk], s[qb][nb]);
+                    s[qb][nb] = mfma16x16x32bf16(sah[nb][kk], qlo[qb][kk], s[qb][nb]);
+                }
+        };
+        // Online softmax with a lazily updated reference: weights are exp2(s - mref) and may
+        // exceed one; mref only moves (and Z, l are rescaled) when a tile's maximum exceeds it
+        // by more than kJump, or on the first tile.  exp2(kJump) times the sequence length is
+        // far inside the float range, so nothing can overflow.
+        auto reference = [&](int qb) __attribute__((always_inline)) {
+            // mask rows past the valid length (register t of block nb is row 16*nb + 4*g + t);
+            // only the last tile of a sequence can need it
+            if (n0 + kNT > len) {
 #pragma unroll
-                        for (int qb = 0; qb < kQB; ++qb) s[qb][nb][t] = -INFINITY;
-                    }
-        }
-        // online softmax per query (= lane column); weights rounded to bf16 and packed as
-        // the B operand of the next product: slot (g, u) of chunk kb is row
-        // 32*kb + 16*(u/4) + 4*g + u%4
+                for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (n0 + 16 * nb + 4 * g + t >= len) s[qb][nb][t] = -INFINITY;
+            }
+            float v = -INFINITY;
+#pragma unroll
+            for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) v = fmaxf(v, s[qb][nb][t]);
+            v = wave_xor_max(v, 16);
+            v = wave_xor_max(v, 32);   // tile maximum relative to mref; finite: a tile has a valid row
+            const bool first = mref[qb] == -INFINITY;
+            if (__any(first || v > kJump)) {   // uniform over the wave, rare
+                const float shift = (first || v > kJump) ? v : 0.f;
+                const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-shift);
+                mref[qb] = (first ? 0.f : mref[qb]) + shift;
+#pragma unroll
+                for (int nb = 0; nb < kNT / 16; ++nb) s[qb][nb] -= shift;
+                lacc[qb] *= alpha;
+#pragma unroll
+                for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= alpha;
+            }
+        };
+        // weights rounded to bf16 and packed as the B operand of the next product: slot
+        // (g, u) of chunk kb is row 32*kb + 16*(u/4) + 4*g + u%4
         v4u wp[kQB][kNT / 32];
-#pragma unroll
-        for (int qb = 0; qb < kQB; ++qb) {
-            float mt = -INFINITY;
-#pragma unroll
-            for (int nb = 0; nb < kNT / 16; ++nb)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) mt = fmaxf(mt, s[qb][nb][t]);
-            mt = wave_xor_max(mt, 16);
-            mt = wave_xor_max(mt, 32);
-            const float mnew = fmaxf(mrun[qb], mt);   // finite: every tile has a valid row
-            const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - mnew);
-            mrun[qb] = mnew;
+        auto weights = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
             for (int kb = 0; kb < kNT / 32; ++kb) {
                 float w[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) w[u] = __builtin_amdgcn_exp2f(s[qb][2 * kb + u / 4][u % 4] - mnew);
+                for (int u = 0; u < 8; ++u) w[u] = __builtin_amdgcn_exp2f(s[qb][2 * kb + u / 4][u % 4]);
                 wp[qb][kb] = v4u{pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]),
                                  pack_bf16(w[6], w[7])};
             }
-            lacc[qb] *= alpha;
+        };
+        // Z(q): Z^T += P^T W^T and the row sums l += 1^T W^T
+        v4u zah[kNT / 32][RB], zal[kNT / 32][RB];
+        auto load_zops = [&]() __attribute__((always_inline)) {
 #pragma unroll
-            for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= alpha;
-        }
-        // Z^T += P^T W^T and the row sums l += 1^T W^T
+            for (int kb = 0; kb < kNT / 32; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < kNT / 32; ++kb) {
+                for (int ib = 0; ib < RB; ++ib) {
+                    const int off = (16 * ib + i16) * LDT + 32 * kb + 4 * g;
+                    const uint2 h0 = *reinterpret_cast<const uint2*>(thi + off);
+                    const uint2 h1 = *reinterpret_cast<const uint2*>(thi + off + 16);
+                    const uint2 l0 = *reinterpret_cast<const uint2*>(tlo + off);
+                    const uint2 l1 = *reinterpret_cast<const uint2*>(tlo + off + 16);
+                    zah[kb][ib] = v4u{h0.x, h0.y, h1.x, h1.y};
+                    zal[kb][ib] = v4u{l0.x, l0.y, l1.x, l1.y};
+                }
+        };
+        auto accumulate = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
-            for (int qb = 0; qb < kQB; ++qb) lacc[qb] = mfma16x16x32bf16(ones, wp[qb][kb], lacc[qb]);
+            for (int kb = 0; kb < kNT / 32; ++kb) {
+                lacc[qb] = mfma16x16x32bf16(ones, wp[qb][kb], lacc[qb]);
 #pragma unroll
-            for (int ib = 0; ib < RB; ++ib) {
-                const int off = (16 * ib + i16) * LDT + 32 * kb + 4 * g;
-                const uint2 h0 = *reinterpret_cast<const uint2*>(thi + off);
-                const uint2 h1 = *reinterpret_cast<const uint2*>(thi + off + 16);
-                const uint2 l0 = *reinterpret_cast<const uint2*>(tlo + off);
-                const uint2 l1 = *reinterpret_cast<const uint2*>(tlo + off + 16);
-                const v4u ah = v4u{h0.x, h0.y, h1.x, h1.y};
-                const v4u al = v4u{l0.x, l0.y, l1.x, l1.y};
-#pragma unroll
-                for (int qb = 0; qb < kQB; ++qb) {
-                    z[qb][ib] = mfma16x16x32bf16(ah, wp[qb][kb], z[qb][ib]);
-                    z[qb][ib] = mfma16x16x32bf16(al, wp[qb][kb], z[qb][ib]);
+                for (int ib = 0; ib < RB; ++ib) {
+                    z[qb][ib] = mfma16x16x32bf16(zah[kb][ib], wp[qb][kb], z[qb][ib]);
+                    z[qb][ib] = mfma16x16x32bf16(zal[kb][ib], wp[qb][kb], z[qb][ib]);
                 }
             }
+        };
+        constexpr int kSMfma = (kNT / 16) * RB2 * 3;            // MFMAs of one S(q)
+        constexpr int kZMfma = (kNT / 32) * (1 + 2 * RB);       // MFMAs of one Z(q)
+
+        scores(0);
+        reference(0);
+        // S(1) on the matrix unit under exp(0) on the vector ALU
+        scores(1);
+        load_zops();
+        weights(0);
+#pragma unroll
+        for (int i = 0; i < kSMfma; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // two VALU
         }
+        reference(1);
+        // Z(0) under exp(1)
+        accumulate(0);
+        weights(1);
+#pragma unroll
+        for (int i = 0; i < kZMfma; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+        }
+        // Z(1) under the split of the next tile
+        accumulate(1);
         if (more) commit(tiles + ((tile + 1) & 1) * kBuf);
         __syncthreads();
     }
@@ -301,7 +368,7 @@ hipError_t launch_t(const void* Q, const float* V, const float* P, const int32_t
                     int N, int r, int M, float scale, bool bf16, float* O, hipStream_t stream) {
     constexpr int RP = 32 * RB2;
     const size_t lds = sizeof(float) * (size_t)D * (RP + 4) +
-                       sizeof(uint16_t) * 2 * (2 * (size_t)kNT * (RP + 8) + 2 * (size_t)RP * (kNT + 8));
+                       sizeof(uint16_t) * 2 * (2 * (size_t)kNT * (RP + SOLAR_ATTN_RPAD) + 2 * (size_t)RP * (kNT + 12));
     dim3 grid(ceil_div(M, kWaves * kQB * 16), B), block(kThreads);
     if (bf16) {
         auto kern = attention_seq_bf16_kernel<D, RB2, true>;
