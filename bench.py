@@ -65,6 +65,8 @@ def main() -> int:
     ap.add_argument("--workload", default=WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-users", type=int, default=8)
+    ap.add_argument("--streams", type=int, default=N_BUFFER_SETS,
+                    help="independent batches in flight (one HIP stream and one buffer set each)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (users are independent, so more GPUs "
@@ -82,15 +84,35 @@ def main() -> int:
     bf16 = w.dtype == synth.BF16
     sets = [binding.DeviceBatch(w.X, w.Q, w.lengths, w.r, bf16) for _ in range(N_BUFFER_SETS)]
     scale = 1.0
+    # Steps are independent batches.  Step i runs on stream i % n_streams with buffer set
+    # i % N_BUFFER_SETS (its own inputs, outputs and workspace), so the latency-bound
+    # eigen-iteration of one batch overlaps the bandwidth/ALU-bound phases of its neighbours.
+    n_streams = max(1, min(args.streams, N_BUFFER_SETS))
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
 
     def step(i):
         db = sets[i % N_BUFFER_SETS]
-        db.factorize()
-        db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
+        with torch.cuda.stream(streams[i % n_streams]):
+            db.factorize()
+            db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
 
-    for i in range(args.warmup):
+    for i in range(max(args.warmup, 1)):
         step(i)
     torch.cuda.synchronize()
+
+    # latency of one step on its own (no overlap with neighbours), and its phases
+    lat_ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    binding.solar_phase_timing_begin()
+    with torch.cuda.stream(streams[0]):
+        lat_ev[0].record()
+        sets[0].factorize()
+        lat_ev[1].record()
+        sets[0].attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
+        lat_ev[2].record()
+    torch.cuda.synchronize()
+    _, solo_phase = binding.solar_phase_timing_end()
+    solo = {"gram": solo_phase[0], "eig": solo_phase[1], "project": solo_phase[2],
+            "attention": lat_ev[1].elapsed_time(lat_ev[2]), "step": lat_ev[0].elapsed_time(lat_ev[2])}
 
     attn_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                for _ in range(args.steps)]
@@ -100,12 +122,17 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     start.record()
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
     for i in range(args.steps):
         db = sets[i % N_BUFFER_SETS]
-        db.factorize()
-        attn_ev[i][0].record()
-        db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
-        attn_ev[i][1].record()
+        with torch.cuda.stream(streams[i % n_streams]):
+            db.factorize()
+            attn_ev[i][0].record()
+            db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
+            attn_ev[i][1].record()
+    for st in streams:
+        torch.cuda.current_stream().wait_stream(st)
     stop.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -160,6 +187,7 @@ def main() -> int:
                                f"{'bf16' if bf16 else 'f32'} inputs, mode 0, scale {scale}",
                    "recipe": w.recipe, "buffer_sets": N_BUFFER_SETS},
         "phase_ms": phases, "dominant_phase": dominant, "host_wall_ms_per_step": wall * 1e3 / args.steps,
+        "streams": n_streams, "single_step_latency_ms": solo,
         "users_not_converged": info_bad,
         "roofline": roof,
     }

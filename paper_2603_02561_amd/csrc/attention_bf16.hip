@@ -25,6 +25,8 @@
 // the row maximum is folded into the accumulator start value of the score MFMA.
 // Eight waves per workgroup (two per SIMD) let the matrix unit of one wave run
 // under the exponentials of the other.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -198,7 +200,10 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     if (ntiles > 0) { fetch(0); commit(tiles); }
     __syncthreads();
 
-    for (int tile = 0; tile < ntiles; ++tile) {
+    // One tile of the sequence.  MASKED is only instantiated for the ragged last tile, so the
+    // full tiles carry no per-score select.
+    auto do_tile = [&](int tile, auto masked_tag) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         const uint16_t* buf = tiles + (tile & 1) * kBuf;
         const uint16_t* rhi = buf;
         const uint16_t* rlo = buf + kImg;
@@ -245,9 +250,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         // by more than kJump, or on the first tile.  exp2(kJump) times the sequence length is
         // far inside the float range, so nothing can overflow.
         auto reference = [&](int qb) __attribute__((always_inline)) {
-            // mask rows past the valid length (register t of block nb is row 16*nb + 4*g + t);
-            // only the last tile of a sequence can need it
-            if (n0 + kNT > len) {
+            // mask rows past the valid length (register t of block nb is row 16*nb + 4*g + t)
+            if constexpr (MASKED) {
 #pragma unroll
                 for (int nb = 0; nb < kNT / 16; ++nb)
 #pragma unroll
@@ -340,7 +344,10 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         accumulate(1);
         if (more) commit(tiles + ((tile + 1) & 1) * kBuf);
         __syncthreads();
-    }
+    };
+    const int nfull = len / kNT;
+    for (int tile = 0; tile < nfull; ++tile) do_tile(tile, std::false_type{});
+    if (nfull < ntiles) do_tile(nfull, std::true_type{});
 
     // ---- epilogue in float: O^T = V (Z / l)^T ------------------------------------------
 #pragma unroll
