@@ -199,6 +199,159 @@ __global__ __launch_bounds__(256) void gram_finalize_kernel(const float* __restr
     G[(size_t)b * D * D + e] = acc;
 }
 
+// ---- d = 256 ---------------------------------------------------------------------------
+// 136 fragment pairs do not fit one wave's accumulators, so G is cut into the four 128 x 128
+// blocks of its 2 x 2 block form and a workgroup (blockIdx.z = job) forms one of
+//   job 0: G00 = X0^T X0 (36 symmetric pairs)     job 1: G11 = X1^T X1 (36 pairs)
+//   job 2: G01 = X0^T X1, fragments s1 = 0..3 of X0 against all 8 of X1 (32 pairs)
+//   job 3: the same for s1 = 4..7
+// with X0, X1 the left and right 128 columns.  G10 is the mirror image of G01.
+constexpr int kGram256Pairs = 36;   // partial slots per job (jobs 2, 3 use 32 of them)
+
+template <bool BF16>
+__global__ __launch_bounds__(kGramWaves * 64) void gram256_partial_kernel(
+    const void* __restrict__ Xv, const int32_t* __restrict__ lengths, int N, int nsplit,
+    float* __restrict__ partials) {
+    constexpr int D = 256, CPL = 8, NP = kGram256Pairs;
+    constexpr int STEP = BF16 ? 32 : 16;
+    const int b = blockIdx.y, split = blockIdx.x, job = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 15, h = lane >> 4;
+    const int len = user_len(lengths, b, N);
+    const int chunk = ceil_div(ceil_div(len, nsplit), STEP) * STEP;
+    const int r0 = split * chunk;
+    const int r1 = min(len, r0 + chunk);
+    const bool cross = job >= 2;
+    const int colA = (job == 1) ? 128 : 0;          // half that supplies the A fragments
+    const int colB = (job == 0) ? 0 : 128;          // half that supplies the B fragments
+    const int sa0 = (job == 3) ? 4 : 0;             // first A fragment of a cross job
+
+    v4f acc[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) acc[p] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    auto mma = [&](auto& fa, auto& fb) __attribute__((always_inline)) {
+        // fa, fb: the eight fragments of the A half and of the B half for this k-step
+        if (!cross) {
+            int p = 0;
+#pragma unroll
+            for (int s1 = 0; s1 < CPL; ++s1)
+#pragma unroll
+                for (int s2 = s1; s2 < CPL; ++s2) {
+                    if constexpr (BF16) acc[p] = mfma16x16x32bf16(fa[s1], fa[s2], acc[p]);
+                    else acc[p] = mfma16x16x4(fa[s1], fa[s2], acc[p]);
+                    ++p;
+                }
+        } else {
+#pragma unroll
+            for (int s1 = 0; s1 < 4; ++s1)
+#pragma unroll
+                for (int s2 = 0; s2 < CPL; ++s2) {
+                    if constexpr (BF16) {
+                        const v4u a = sa0 ? fa[s1 + 4] : fa[s1];
+                        acc[s1 * CPL + s2] = mfma16x16x32bf16(a, fb[s2], acc[s1 * CPL + s2]);
+                    } else {
+                        const float a = sa0 ? fa[s1 + 4] : fa[s1];
+                        acc[s1 * CPL + s2] = mfma16x16x4(a, fb[s2], acc[s1 * CPL + s2]);
+                    }
+                }
+        }
+    };
+
+    if constexpr (BF16) {
+        const uint32_t* X = reinterpret_cast<const uint32_t*>(Xv) + (size_t)b * N * (D / 2);
+        auto load_frags = [&](v4u (&frag)[CPL], int base, int col0) __attribute__((always_inline)) {
+            uint32_t in[8][4];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int row = base + 8 * h + t;
+                v4u v = v4u{0u, 0u, 0u, 0u};
+                if (row < r1) v = *reinterpret_cast<const v4u*>(X + (size_t)row * (D / 2) + col0 / 2 + 4 * j);
+                in[t][0] = v.x; in[t][1] = v.y; in[t][2] = v.z; in[t][3] = v.w;
+            }
+#pragma unroll
+            for (int s = 0; s < CPL; ++s) {
+                uint32_t o[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t a = in[2 * u][s / 2], c = in[2 * u + 1][s / 2];
+                    o[u] = (s & 1) ? ((a >> 16) | (c & 0xffff0000u)) : ((a & 0xffffu) | (c << 16));
+                }
+                frag[s] = v4u{o[0], o[1], o[2], o[3]};
+            }
+        };
+        for (int base = r0 + wave * STEP; base < r1; base += kGramWaves * STEP) {
+            v4u fa[CPL], fb[CPL];
+            load_frags(fa, base, colA);
+            if (cross) load_frags(fb, base, colB);
+            mma(fa, fb);
+        }
+    } else {
+        const float* X = reinterpret_cast<const float*>(Xv) + (size_t)b * N * D;
+        for (int base = r0 + wave * STEP; base < r1; base += kGramWaves * STEP) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int row = base + 4 * t + h;
+                float fa[CPL], fb[CPL];
+#pragma unroll
+                for (int q = 0; q < CPL / 4; ++q) {
+                    v4f va = v4f{0.f, 0.f, 0.f, 0.f}, vb = va;
+                    if (row < r1) {
+                        va = *reinterpret_cast<const v4f*>(X + (size_t)row * D + colA + CPL * j + 4 * q);
+                        if (cross) vb = *reinterpret_cast<const v4f*>(X + (size_t)row * D + colB + CPL * j + 4 * q);
+                    }
+                    fa[4 * q + 0] = va.x; fa[4 * q + 1] = va.y; fa[4 * q + 2] = va.z; fa[4 * q + 3] = va.w;
+                    fb[4 * q + 0] = vb.x; fb[4 * q + 1] = vb.y; fb[4 * q + 2] = vb.z; fb[4 * q + 3] = vb.w;
+                }
+                mma(fa, fb);
+            }
+        }
+    }
+
+    __shared__ v4f red[NP * 64];
+    for (int w = 0; w < kGramWaves; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                if (w == 0) red[p * 64 + lane] = acc[p];
+                else red[p * 64 + lane] += acc[p];
+            }
+        }
+        __syncthreads();
+    }
+    v4f* out = reinterpret_cast<v4f*>(partials) + (((size_t)b * nsplit + split) * 4 + job) * (NP * 64);
+    for (int i = threadIdx.x; i < NP * 64; i += kGramWaves * 64) out[i] = red[i];
+}
+
+__global__ __launch_bounds__(256) void gram256_finalize_kernel(const float* __restrict__ partials,
+                                                               int nsplit, float* __restrict__ G) {
+    constexpr int D = 256, CPL = 8, NP = kGram256Pairs;
+    const int b = blockIdx.y;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= D * D) return;
+    int a = e / D, c = e % D;
+    if (a / 128 > c / 128) { const int t = a; a = c; c = t; }   // lower-left block: mirror
+    const int ha = a / 128, hc = c / 128;
+    int s1 = (a % 128) % CPL, i1 = (a % 128) / CPL, s2 = (c % 128) % CPL, i2 = (c % 128) / CPL;
+    int job, pair;
+    if (ha == hc) {
+        job = ha;
+        if (s1 > s2) {
+            int t = s1; s1 = s2; s2 = t;
+            t = i1; i1 = i2; i2 = t;
+        }
+        pair = s1 * CPL - (s1 * (s1 - 1)) / 2 + (s2 - s1);
+    } else {
+        job = 2 + (s1 >= 4 ? 1 : 0);
+        pair = (s1 % 4) * CPL + s2;
+    }
+    const int off = pair * 256 + (i2 + 16 * (i1 / 4)) * 4 + (i1 % 4);
+    const float* p = partials + ((size_t)b * nsplit * 4 + job) * (NP * 256) + off;
+    float acc = 0.f;
+    for (int s = 0; s < nsplit; ++s) acc += p[(size_t)s * 4 * (NP * 256)];
+    G[(size_t)b * D * D + e] = acc;
+}
+
 int gram_nsplit(int B, int N) {
     // Aim at about two workgroups per compute unit, at least 512 rows per chunk.
     int want = ceil_div(512, B);
@@ -210,6 +363,7 @@ int gram_nsplit(int B, int N) {
 }
 
 size_t gram_partial_floats(int B, int N, int d) {
+    if (d == 256) return (size_t)B * gram_nsplit(B, N) * 4 * kGram256Pairs * 256;
     const int cpl = d / 16;
     return (size_t)B * gram_nsplit(B, N) * (cpl * (cpl + 1) / 2) * 256;
 }
@@ -236,6 +390,19 @@ hipError_t launch_gram(const void* X, const int32_t* lengths, int B, int N, int 
     switch (d) {
         case 64: return launch_gram_t<4>(X, lengths, B, N, bf16, partials, G, stream);
         case 128: return launch_gram_t<8>(X, lengths, B, N, bf16, partials, G, stream);
+        case 256: {
+            const int nsplit = gram_nsplit(B, N);
+            dim3 grid(nsplit, B, 4), block(kGramWaves * 64);
+            if (bf16)
+                hipLaunchKernelGGL((gram256_partial_kernel<true>), grid, block, 0, stream, X, lengths, N,
+                                   nsplit, partials);
+            else
+                hipLaunchKernelGGL((gram256_partial_kernel<false>), grid, block, 0, stream, X, lengths, N,
+                                   nsplit, partials);
+            hipLaunchKernelGGL(gram256_finalize_kernel, dim3(256 * 256 / 256, B), dim3(256), 0, stream,
+                               partials, nsplit, G);
+            return hipGetLastError();
+        }
         default: return hipErrorInvalidValue;
     }
 }

@@ -54,6 +54,9 @@ def small_workloads():
     out.append(("f32_d128_r12_varlen", synth.make_workload("t", 3, 500, 128, 12, 65, synth.F32, "gauss_lowrank",
                                                            var_len=(64, 500), seed=105)))
     out.append(("bf16_d64_r16", synth.make_workload("t", 2, 400, 64, 16, 33, synth.BF16, "gauss_lowrank", seed=106)))
+    out.append(("bf16_d256_r32", synth.make_workload("t", 2, 700, 256, 32, 100, synth.BF16, "gauss_lowrank", seed=107)))
+    out.append(("f32_d256_r16_varlen", synth.make_workload("t", 2, 300, 256, 16, 40, synth.F32, "gauss_lowrank",
+                                                           var_len=(100, 300), seed=108)))
     return out
 
 
