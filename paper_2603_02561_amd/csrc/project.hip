@@ -98,6 +98,106 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(
     }
 }
 
+// bf16 inputs: the rows of X are bf16 already, so a lane's 16-byte load (eight consecutive
+// columns of its row) is the B operand of the 16x16x32 bf16 MFMA as it stands.  V is float:
+// it is split once per wave into a bf16 head and tail (V = hi + lo to 16 bits) that stay in
+// registers as the A operands, and each k-chunk costs two MFMAs.  The next tile of X is
+// fetched while the current one is in the matrix unit.
+template <int D, int RB>
+__global__ __launch_bounds__(kProjThreads) void project_bf16_kernel(
+    const uint16_t* __restrict__ X, const int32_t* __restrict__ lengths, const float* __restrict__ V,
+    int N, int r, float* __restrict__ P) {
+    constexpr int KK = D / 32;
+    const int b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i16 = lane & 15, g = lane >> 4;
+    const int len = user_len(lengths, b, N);
+    const float* Vb = V + (size_t)b * D * r;
+
+    // A operands: slot (g, u) of chunk kk is column 32*kk + 8*g + u; row i16 is rank 16*rb + i16
+    v4u ahi[KK][RB], alo[KK][RB];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int rank = 16 * rb + i16;
+            uint32_t hw[4], lw[4];
+#pragma unroll
+            for (int u2 = 0; u2 < 4; ++u2) {
+                float v0 = 0.f, v1 = 0.f;
+                if (rank < r) {
+                    v0 = Vb[(size_t)(32 * kk + 8 * g + 2 * u2) * r + rank];
+                    v1 = Vb[(size_t)(32 * kk + 8 * g + 2 * u2 + 1) * r + rank];
+                }
+                typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+                const v2bf h = {(__bf16)v0, (__bf16)v1};
+                const v2bf l = {(__bf16)(v0 - (float)h[0]), (__bf16)(v1 - (float)h[1])};
+                hw[u2] = __builtin_bit_cast(uint32_t, h);
+                lw[u2] = __builtin_bit_cast(uint32_t, l);
+            }
+            ahi[kk][rb] = v4u{hw[0], hw[1], hw[2], hw[3]};
+            alo[kk][rb] = v4u{lw[0], lw[1], lw[2], lw[3]};
+        }
+
+    const int rows_per_block = 16 * 4 * kProjTilesPerWave;
+    const int block_row0 = blockIdx.x * rows_per_block;
+    const uint16_t* Xb = X + (size_t)b * N * D;
+    float* Pb = P + (size_t)b * N * r;
+    auto fetch = [&](v4u (&x)[KK], int n0) __attribute__((always_inline)) {
+        const int n = n0 + i16;
+        const bool valid = n < len;
+        const v4u* src = reinterpret_cast<const v4u*>(Xb + (size_t)(valid ? n : 0) * D);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            x[kk] = src[4 * kk + g];
+            if (!valid) x[kk] = v4u{0u, 0u, 0u, 0u};
+        }
+    };
+    v4u cur[KK], nxt[KK];
+    int n0 = block_row0 + wave * 16;
+    if (n0 < len) fetch(cur, n0);
+    for (int tile = 0; tile < kProjTilesPerWave; ++tile) {
+        if (n0 >= N) break;
+        const int n_next = n0 + 64;
+        const bool have_next = tile + 1 < kProjTilesPerWave && n_next < len;
+        if (have_next) fetch(nxt, n_next);
+        const int n = n0 + i16;
+        if (n0 >= len) {
+            // rows past the valid length: P is defined to be zero there
+            for (int e = lane; e < 16 * r; e += 64) {
+                const int rr = n0 + e / r;
+                if (rr < N) Pb[(size_t)rr * r + e % r] = 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    acc = mfma16x16x32bf16(ahi[kk][rb], cur[kk], acc);
+                    acc = mfma16x16x32bf16(alo[kk][rb], cur[kk], acc);
+                }
+                if (n < N) {
+                    const int c0 = 16 * rb + 4 * g;
+                    float* dst = Pb + (size_t)n * r + c0;
+                    if (c0 + 3 < r && (r % 4) == 0) {
+                        *reinterpret_cast<v4f*>(dst) = acc;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (c0 + t < r) dst[t] = acc[t];
+                    }
+                }
+            }
+        }
+        if (have_next) {
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) cur[kk] = nxt[kk];
+        }
+        n0 = n_next;
+    }
+}
+
 }  // namespace
 
 template <int D>
@@ -107,11 +207,25 @@ static hipError_t launch_project_d(const void* X, const int32_t* lengths, const 
     const size_t lds = sizeof(float) * (size_t)D * (RP + 4);
     dim3 grid(ceil_div(N, 16 * 4 * kProjTilesPerWave), B), block(kProjThreads);
     if (bf16) {
-        auto kern = project_kernel<D, true>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, X, lengths, V, N, r, RP, P);
+        const uint16_t* Xh = reinterpret_cast<const uint16_t*>(X);
+        switch (RP / 16) {
+            case 1: hipLaunchKernelGGL((project_bf16_kernel<D, 1>), grid, block, 0, stream, Xh, lengths, V, N, r, P); break;
+            case 2: hipLaunchKernelGGL((project_bf16_kernel<D, 2>), grid, block, 0, stream, Xh, lengths, V, N, r, P); break;
+            case 3: hipLaunchKernelGGL((project_bf16_kernel<D, 3>), grid, block, 0, stream, Xh, lengths, V, N, r, P); break;
+            case 4:
+                if constexpr (D <= 128) {
+                    hipLaunchKernelGGL((project_bf16_kernel<D, 4>), grid, block, 0, stream, Xh, lengths, V, N, r, P);
+                    break;
+                }
+                [[fallthrough]];
+            default: {
+                auto kern = project_kernel<D, true>;
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (e != hipSuccess) return e;
+                hipLaunchKernelGGL(kern, grid, block, lds, stream, X, lengths, V, N, r, RP, P);
+            }
+        }
     } else {
         auto kern = project_kernel<D, false>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
