@@ -22,6 +22,10 @@ if ROOT not in sys.path:
 WORKLOAD = "C3"
 N_BUFFER_SETS = 3   # rotate inputs so that X is not served from the 256 MiB Infinity Cache
 
+# HBM bytes per launch from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` (see the summaries under
+# profiles/ for the commands and the copy-kernel calibration); keyed by (workload, phase).
+MEASURED_TRAFFIC = {}
+
 PEAKS = {
     "hbm_GBps": 8000.0,
     "mfma_f32_TFLOPs": 157.3,
@@ -65,6 +69,8 @@ def main() -> int:
     ap.add_argument("--workload", default=WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-users", type=int, default=8)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 256 MiB device copies (reference for PMC byte counters)")
     ap.add_argument("--streams", type=int, default=N_BUFFER_SETS,
                     help="independent batches in flight (one HIP stream and one buffer set each)")
     args = ap.parse_args()
@@ -80,6 +86,13 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     w = synth.make_config(args.workload)
     bf16 = w.dtype == synth.BF16
     sets = [binding.DeviceBatch(w.X, w.Q, w.lengths, w.r, bf16) for _ in range(N_BUFFER_SETS)]
@@ -143,50 +156,63 @@ def main() -> int:
     ms_per_step = total_ms / args.steps
     info_bad = int((sets[0].info != 0).sum().item())
 
-    # algorithmic work per launch (whole batch), see the design doc
+    # Algorithmic work per launch (whole batch): what the method must move or compute, not
+    # what the kernels happen to do ("Kernels and rooflines").
     lens = w.lengths.astype(np.float64)
     e = 2 if bf16 else 4
-    gram_bytes = float(np.sum(lens) * w.d * e + w.B * w.d * w.d * 4)
-    proj_bytes = float(np.sum(lens) * w.d * e + np.sum(lens) * w.r * 4)
-    attn_flops = float(np.sum(4.0 * w.M * lens * w.r) + w.B * 4.0 * w.M * w.r * w.d)
+    work = {
+        # read X once, write G
+        "gram": ("hbm", float(np.sum(lens) * w.d * e + w.B * w.d * w.d * 4)),
+        # read X once, write P
+        "project": ("hbm", float(np.sum(lens) * w.d * e + np.sum(lens) * w.r * 4)),
+        # Qt = Q V, S = Qt P^T, Z = W P, O = Z V^T
+        "attention": ("mfma", float(np.sum(4.0 * w.M * lens * w.r) + w.B * 4.0 * w.M * w.r * w.d)),
+    }
+    mfma_peak = PEAKS["mfma_bf16_TFLOPs"] if bf16 else PEAKS["mfma_f32_TFLOPs"]
+    kernel_names = {"gram": "gram_partial_kernel (+ gram_finalize_kernel)", "eig": "eig_topr_kernel",
+                    "project": "project_bf16_kernel" if bf16 else "project_kernel",
+                    "attention": "attention_seq_bf16_kernel" if bf16 else "attention_seq_kernel"}
     phases = {"gram": gram_ms, "eig": eig_ms, "project": proj_ms, "attention": attn_ms}
-    dominant = max(phases, key=phases.get)
-    if dominant == "attention":
-        achieved = attn_flops / (attn_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "kernel": "attention_seq_kernel", "achieved": achieved,
-                "peak": PEAKS["mfma_f32_TFLOPs"], "unit": "TFLOP/s",
-                "frac": achieved / PEAKS["mfma_f32_TFLOPs"], "traffic": None}
-    elif dominant == "gram":
-        achieved = gram_bytes / (gram_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "kernel": "gram_partial_kernel", "achieved": achieved,
-                "peak": PEAKS["hbm_GBps"], "unit": "GB/s", "frac": achieved / PEAKS["hbm_GBps"],
-                "traffic": None}
-    elif dominant == "project":
-        achieved = proj_bytes / (proj_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "kernel": "project_kernel", "achieved": achieved,
-                "peak": PEAKS["hbm_GBps"], "unit": "GB/s", "frac": achieved / PEAKS["hbm_GBps"],
-                "traffic": None}
-    else:
-        # the eigen-iteration is latency bound (serial Jacobi rounds, one workgroup per user):
-        # it has no roofline; report the Gram kernel's HBM figure and say which phase dominates
-        achieved = gram_bytes / (gram_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "kernel": "gram_partial_kernel", "achieved": achieved,
-                "peak": PEAKS["hbm_GBps"], "unit": "GB/s", "frac": achieved / PEAKS["hbm_GBps"],
-                "traffic": None,
-                "note": "eig_topr_kernel dominates wall time but is latency bound (no roofline)"}
+    kernels = {}
+    for name, (bound, amount) in work.items():
+        for label, ms in (("pipelined", phases[name]), ("alone", solo[name])):
+            if bound == "hbm":
+                achieved, peak, unit = amount / (ms * 1e-3) / 1e9, PEAKS["hbm_GBps"], "GB/s"
+            else:
+                achieved, peak, unit = amount / (ms * 1e-3) / 1e12, mfma_peak, "TFLOP/s"
+            kernels.setdefault(name, {"kernel": kernel_names[name], "bound": bound, "unit": unit,
+                                      "peak": peak, "algorithmic": amount})[label] = {
+                "ms": ms, "achieved": achieved, "frac": achieved / peak}
+    kernels["eig"] = {"kernel": kernel_names["eig"], "bound": "latency (serial Jacobi rounds, one "
+                      "workgroup per user; no roofline)", "pipelined": {"ms": eig_ms},
+                      "alone": {"ms": solo["eig"]}}
+    # dominant kernel = the roofline-bound kernel with the most GPU time in the timed region
+    dominant = max(work, key=lambda k: phases[k])
+    traffic = MEASURED_TRAFFIC.get((w.name, dominant))
+    roof = {"kernel": kernel_names[dominant], "bound": kernels[dominant]["bound"],
+            "achieved": kernels[dominant]["pipelined"]["achieved"], "peak": kernels[dominant]["peak"],
+            "unit": kernels[dominant]["unit"], "frac": kernels[dominant]["pipelined"]["frac"],
+            "traffic": traffic,
+            "achieved_alone": kernels[dominant]["alone"]["achieved"],
+            "frac_alone": kernels[dominant]["alone"]["frac"],
+            "note": "durations are HIP-event times inside the timed region, where kernels of "
+                    f"{n_streams} independent batches share the GPU; *_alone is the same launch with "
+                    "nothing else running. eig_topr_kernel has the longest single launch but is "
+                    "latency bound and runs under the other phases."}
 
     out = {
-        "metric": "user-sequences/sec (factorize+attend) at N=10k,d=128,r=32,M=1000",
+        "metric": "user-sequences/sec (factorize+attend) at N=10k,d=128,r=32,M=1000; % roofline",
         "value": w.B * args.steps / (total_ms * 1e-3),
         "unit": "user-sequences/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 inputs, f32 arithmetic" if bf16 else "f32",
+        "vs_baseline": None, "dtype": "bf16 inputs, f32 accumulate" if bf16 else "f32",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} N={w.N} d={w.d} r={w.r} M={w.M} "
                                f"{'bf16' if bf16 else 'f32'} inputs, mode 0, scale {scale}",
                    "recipe": w.recipe, "buffer_sets": N_BUFFER_SETS},
-        "phase_ms": phases, "dominant_phase": dominant, "host_wall_ms_per_step": wall * 1e3 / args.steps,
+        "phase_ms": phases, "dominant_kernel": dominant, "kernels": kernels,
+        "host_wall_ms_per_step": wall * 1e3 / args.steps,
         "streams": n_streams, "single_step_latency_ms": solo,
         "users_not_converged": info_bad,
         "roofline": roof,

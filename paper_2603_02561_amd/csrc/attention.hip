@@ -37,18 +37,23 @@ __device__ __forceinline__ int rank_perm(int i) { return (i >> 2) + 4 * (i & 3);
 template <int D, int RB, bool BF16>
 __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
     const void* __restrict__ Qv, const float* __restrict__ V, const float* __restrict__ P,
-    const int32_t* __restrict__ lengths, int N, int r, int M, float scale, float* __restrict__ O) {
+    const int32_t* __restrict__ lengths, int B, int N, int r, int M, float scale, float* __restrict__ O) {
     constexpr int RP = 16 * RB;
     constexpr int LDV = RP + 4;
     constexpr int LDP = RP + 4;
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                       // [D][LDV]
     float* Ps = Vs + D * LDV;               // [2][kNT][LDP]
-    const int b = blockIdx.y;
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id.  All M-tiles of a user
+    // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
+    const int mtiles = ceil_div(M, 4 * kQB * 16);
+    const int slot = blockIdx.x >> 3;
+    const int b = (slot / mtiles) * 8 + (blockIdx.x & 7);
+    if (b >= B) return;   // uniform over the workgroup
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, g = lane >> 4;
     const int len = user_len(lengths, b, N);
-    const int m_wave = blockIdx.x * (4 * kQB * 16) + wave * (kQB * 16);
+    const int m_wave = (slot % mtiles) * (4 * kQB * 16) + wave * (kQB * 16);
     const float* Pb = P + (size_t)b * N * r;
 
     for (int e = tid; e < D * RP; e += kAttnThreads) {
@@ -287,19 +292,19 @@ static hipError_t launch_seq_t(const void* Q, const float* V, const float* P,
                                bool bf16, float* O, hipStream_t stream) {
     constexpr int RP = 16 * RB;
     const size_t lds = sizeof(float) * ((size_t)D * (RP + 4) + 2 * kNT * (RP + 4));
-    dim3 grid(ceil_div(M, 4 * kQB * 16), B), block(kAttnThreads);
+    dim3 grid(ceil_div(M, 4 * kQB * 16) * 8 * ceil_div(B, 8)), block(kAttnThreads);
     if (bf16) {
         auto kern = attention_seq_kernel<D, RB, true>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, N, r, M, scale, O);
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
     } else {
         auto kern = attention_seq_kernel<D, RB, false>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, N, r, M, scale, O);
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
     }
     return hipGetLastError();
 }

@@ -62,7 +62,7 @@ __device__ __forceinline__ void split_bf16(float x, float& hi, float& lo) {
 template <int D, int RB2, bool BF16>
 __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     const void* __restrict__ Qv, const float* __restrict__ V, const float* __restrict__ P,
-    const int32_t* __restrict__ lengths, int N, int r, int M, float scale, float* __restrict__ O) {
+    const int32_t* __restrict__ lengths, int B, int N, int r, int M, float scale, float* __restrict__ O) {
     constexpr int RP = 32 * RB2;          // padded rank
     constexpr int RB = RP / 16;
     constexpr int LDV = RP + 4;           // floats
@@ -77,11 +77,16 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                                             // [D][LDV]
     uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);  // [2][kBuf]
-    const int b = blockIdx.y;
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id.  All M-tiles of a user
+    // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
+    const int mtiles = ceil_div(M, kWaves * kQB * 16);
+    const int slot = blockIdx.x >> 3;
+    const int b = (slot / mtiles) * 8 + (blockIdx.x & 7);
+    if (b >= B) return;   // uniform over the workgroup
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, g = lane >> 4;
     const int len = user_len(lengths, b, N);
-    const int m_wave = blockIdx.x * (kWaves * kQB * 16) + wave * (kQB * 16);
+    const int m_wave = (slot % mtiles) * (kWaves * kQB * 16) + wave * (kQB * 16);
     const float* Pb = P + (size_t)b * N * r;
 
     for (int e = tid; e < D * RP; e += kThreads) {
@@ -288,9 +293,12 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                 for (int u = 0; u < 8; ++u) w[u] = __builtin_amdgcn_exp2f(s[qb][2 * kb + u / 4][u % 4]);
                 wp[qb][kb] = v4u{pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]),
                                  pack_bf16(w[6], w[7])};
+                // row sums l += 1^T W^T (issued here so that the weights are produced in this
+                // stage, next to the other query block's matrix work)
+                lacc[qb] = mfma16x16x32bf16(ones, wp[qb][kb], lacc[qb]);
             }
         };
-        // Z(q): Z^T += P^T W^T and the row sums l += 1^T W^T
+        // Z(q): Z^T += P^T W^T
         v4u zah[kNT / 32][RB], zal[kNT / 32][RB];
         auto load_zops = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -309,16 +317,17 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         auto accumulate = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
             for (int kb = 0; kb < kNT / 32; ++kb) {
-                lacc[qb] = mfma16x16x32bf16(ones, wp[qb][kb], lacc[qb]);
 #pragma unroll
                 for (int ib = 0; ib < RB; ++ib) {
                     z[qb][ib] = mfma16x16x32bf16(zah[kb][ib], wp[qb][kb], z[qb][ib]);
+#ifndef SOLAR_ATTN_ZHI_ONLY
                     z[qb][ib] = mfma16x16x32bf16(zal[kb][ib], wp[qb][kb], z[qb][ib]);
+#endif
                 }
             }
         };
         constexpr int kSMfma = (kNT / 16) * RB2 * 3;            // MFMAs of one S(q)
-        constexpr int kZMfma = (kNT / 32) * (1 + 2 * RB);       // MFMAs of one Z(q)
+        constexpr int kZMfma = (kNT / 32) * (2 * RB);           // MFMAs of one Z(q)
 
         scores(0);
         reference(0);
@@ -376,19 +385,19 @@ hipError_t launch_t(const void* Q, const float* V, const float* P, const int32_t
     constexpr int RP = 32 * RB2;
     const size_t lds = sizeof(float) * (size_t)D * (RP + 4) +
                        sizeof(uint16_t) * 2 * (2 * (size_t)kNT * (RP + SOLAR_ATTN_RPAD) + 2 * (size_t)RP * (kNT + 12));
-    dim3 grid(ceil_div(M, kWaves * kQB * 16), B), block(kThreads);
+    dim3 grid(ceil_div(M, kWaves * kQB * 16) * 8 * ceil_div(B, 8)), block(kThreads);
     if (bf16) {
         auto kern = attention_seq_bf16_kernel<D, RB2, true>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, N, r, M, scale, O);
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
     } else {
         auto kern = attention_seq_bf16_kernel<D, RB2, false>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, N, r, M, scale, O);
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
     }
     return hipGetLastError();
 }

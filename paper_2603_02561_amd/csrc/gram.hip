@@ -175,10 +175,8 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
     for (int i = threadIdx.x; i < NP * 64; i += kGramWaves * 64) out[i] = red[i];
 }
 
-// Sum of the per-chunk partial blocks in a fixed order, and the inverse of the fragment
-// permutation.  A thread owns one element of the partial layout (coalesced reads), i.e.
-// element (i1, i2) of fragment pair (s1 <= s2) = G[CPL*i1+s1][CPL*i2+s2]; for s1 < s2 it
-// also writes the mirror image (a diagonal pair holds both halves itself).
+// G[b][a][c] = sum over chunks of the partial block element that holds (a, c) or,
+// below the diagonal of fragment pairs, its mirror image (c, a).
 template <int CPL>
 __global__ __launch_bounds__(256) void gram_finalize_kernel(const float* __restrict__ partials,
                                                             int nsplit, float* __restrict__ G) {
@@ -186,19 +184,19 @@ __global__ __launch_bounds__(256) void gram_finalize_kernel(const float* __restr
     constexpr int NP = gram_pairs<CPL>();
     const int b = blockIdx.y;
     const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= NP * 256) return;
-    const float* p = partials + (size_t)b * nsplit * (NP * 256) + e;
+    if (e >= D * D) return;
+    int a = e / D, c = e % D;
+    int s1 = a % CPL, i1 = a / CPL, s2 = c % CPL, i2 = c / CPL;
+    if (s1 > s2) {
+        int t = s1; s1 = s2; s2 = t;
+        t = i1; i1 = i2; i2 = t;
+    }
+    const int pair = s1 * CPL - (s1 * (s1 - 1)) / 2 + (s2 - s1);
+    const int off = pair * 256 + (i2 + 16 * (i1 / 4)) * 4 + (i1 % 4);
+    const float* p = partials + (size_t)b * nsplit * (NP * 256) + off;
     float acc = 0.f;
     for (int s = 0; s < nsplit; ++s) acc += p[(size_t)s * (NP * 256)];
-    const int pair = e / 256, lane = (e % 256) / 4, t = e % 4;
-    int s1 = 0, rem = pair;
-    while (rem >= CPL - s1) { rem -= CPL - s1; ++s1; }
-    const int s2 = s1 + rem;
-    const int i1 = 4 * (lane / 16) + t, i2 = lane % 16;
-    const int a = CPL * i1 + s1, c = CPL * i2 + s2;
-    float* Gb = G + (size_t)b * D * D;
-    Gb[a * D + c] = acc;
-    if (s1 != s2) Gb[c * D + a] = acc;
+    G[(size_t)b * D * D + e] = acc;
 }
 
 // ---- d = 256 ---------------------------------------------------------------------------
@@ -382,7 +380,7 @@ static hipError_t launch_gram_t(const void* X, const int32_t* lengths, int B, in
         hipLaunchKernelGGL((gram_partial_kernel<CPL, false>), grid, block, 0, stream, X, lengths, N,
                            nsplit, partials);
     constexpr int D = 16 * CPL;
-    dim3 g2(gram_pairs<CPL>(), B);
+    dim3 g2(ceil_div(D * D, 256), B);
     hipLaunchKernelGGL((gram_finalize_kernel<CPL>), g2, dim3(256), 0, stream, partials, nsplit, G);
     return hipGetLastError();
 }
