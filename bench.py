@@ -24,7 +24,12 @@ N_BUFFER_SETS = 3   # rotate inputs so that X is not served from the 256 MiB Inf
 
 # HBM bytes per launch from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` (see the summaries under
 # profiles/ for the commands and the copy-kernel calibration); keyed by (workload, phase).
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/hbm_traffic_C3.txt: fetch + write bytes of one launch
+    ("C3", "attention"): 99.6e6 + 33.0e6,
+    ("C3", "gram"): 164.1e6 + 18.9e6 + 62.9e6 + 4.2e6,
+    ("C3", "project"): 172.6e6 + 82.7e6,
+}
 
 PEAKS = {
     "hbm_GBps": 8000.0,
