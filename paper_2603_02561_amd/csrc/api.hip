@@ -162,10 +162,13 @@ solar_status solar_svd_attention(const void* Q, const float* S, const float* V, 
     switch (mode) {
         case SOLAR_ATTN_SEQ_SOFTMAX:
             if (!P) return SOLAR_ERR_INVALID_ARG;
-            // bf16 inputs take the bf16 matrix-unit path (split operands, about 16 mantissa
-            // bits in the scores); float inputs keep float arithmetic throughout
+            // bf16 inputs take a 16-bit matrix-unit path: single fp16 operands by default
+            // (2e-2 contract), bf16 head + tail operands (about 16 mantissa bits in the scores)
+            // when SOLAR_ATTN_SPLIT is set or S is not supplied; float inputs keep float
+            // arithmetic throughout
             if (bf16 && attention_seq_bf16_supported(d, r) && !std::getenv("SOLAR_ATTN_F32"))
-                e = launch_attention_seq_bf16(Q, V, P, lengths, B, N, d, r, M, scale, bf16, O, st);
+                e = launch_attention_seq_bf16(Q, S, V, P, lengths, B, N, d, r, M, scale,
+                                              std::getenv("SOLAR_ATTN_SPLIT") != nullptr, O, st);
             else
                 e = launch_attention_seq(Q, V, P, lengths, B, N, d, r, M, scale, bf16, O, st);
             break;

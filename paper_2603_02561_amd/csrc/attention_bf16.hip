@@ -12,6 +12,12 @@
 // normalization is consistent with the weights actually used and needs neither a
 // VALU add per score nor a cross-lane reduction.
 //
+// A second, faster variant (PREC = 1) rounds P, Qt and the weights to fp16 once (11-bit
+// significands; P is first scaled by 1/S[0] so that it lies in [-1, 1]) and needs one MFMA
+// where the split variant needs three or two.  Its scores carry about 2^-11 relative error
+// (<= ~1e-2 absolute at scores of 20), which stays inside the 2e-2 contract for bf16 inputs;
+// it is the default for bf16 inputs when S is supplied.
+//
 // As in the float kernel the products are evaluated transposed (S^T = P Qt^T,
 // Z^T = P^T W^T) so that a query is a lane: accumulators of one product are the B
 // operand of the next without any data movement, because the contraction index can
@@ -45,7 +51,6 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kQB = 2;    // 16-query blocks per wave
 constexpr int kNT = SOLAR_ATTN_NT;   // rows of P per tile
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kJump = 16.f;   // log2 units a tile maximum may exceed the reference by
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     // round to nearest even; inputs are finite
@@ -59,10 +64,39 @@ __device__ __forceinline__ void split_bf16(float x, float& hi, float& lo) {
     lo = x - hi;
 }
 
-template <int D, int RB2, bool BF16>
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ v4f mfma16x16x32f16(v4u a, v4u b, v4f c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c,
+                                                  0, 0, 0);
+}
+
+// two floats -> packed fp16, round to nearest even (operands that are prepared once)
+__device__ __forceinline__ uint32_t pack_f16(float a, float b) {
+    v2h v = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// two floats -> packed fp16 in one instruction, round toward zero (softmax weights; their
+// row sum is taken from the rounded values, so the rounding direction cancels)
+__device__ __forceinline__ uint32_t pack_f16_rtz(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+
+template <int PREC>
+__device__ __forceinline__ v4f mma(v4u a, v4u b, v4f c) {
+    if constexpr (PREC == 0) return mfma16x16x32bf16(a, b, c);
+    else return mfma16x16x32f16(a, b, c);
+}
+
+template <int D, int RB2, bool BF16, int PREC>
 __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
-    const void* __restrict__ Qv, const float* __restrict__ V, const float* __restrict__ P,
-    const int32_t* __restrict__ lengths, int B, int N, int r, int M, float scale, float* __restrict__ O) {
+    const void* __restrict__ Qv, const float* __restrict__ S, const float* __restrict__ V,
+    const float* __restrict__ P, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
+    float scale, float* __restrict__ O) {
+    constexpr int NIMG = PREC == 0 ? 2 : 1;   // images per layout: head (+ tail)
+    constexpr float kJump = PREC == 0 ? 16.f : 8.f;   // log2 units a tile maximum may exceed the reference by
     constexpr int RP = 32 * RB2;          // padded rank
     constexpr int RB = RP / 16;
     constexpr int LDV = RP + 4;           // floats
@@ -73,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     constexpr int LDT = kNT + 12;         // bf16 elements, transposed image [RP][LDT]
     constexpr int kImg = kNT * LDR;       // elements of one row-major image
     constexpr int kImgT = RP * LDT;       // elements of one transposed image
-    constexpr int kBuf = 2 * kImg + 2 * kImgT;   // hi, lo row-major; hi, lo transposed
+    constexpr int kBuf = NIMG * (kImg + kImgT);  // row-major head (, tail); transposed head (, tail)
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                                             // [D][LDV]
     uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);  // [2][kBuf]
@@ -88,6 +122,12 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     const int len = user_len(lengths, b, N);
     const int m_wave = (slot % mtiles) * (kWaves * kQB * 16) + wave * (kQB * 16);
     const float* Pb = P + (size_t)b * N * r;
+    // PREC 1: P is scaled into [-1, 1] by the largest singular value before it is rounded
+    float pscale = 1.f, punscale = 1.f;
+    if constexpr (PREC == 1) {
+        const float s0 = S[(size_t)b * r];
+        if (s0 > 0.f) { pscale = 1.f / s0; punscale = s0; }
+    }
 
     for (int e = tid; e < D * RP; e += kThreads) {
         const int k = e / RP, c = e % RP;
@@ -128,11 +168,20 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         // 32*kk + 16*(u/4) + 4*g + u%4, i.e. registers of blocks 2*kk and 2*kk+1
 #pragma unroll
         for (int kk = 0; kk < RB2; ++kk) {
-            float h[8], l[8];
+            if constexpr (PREC == 0) {
+                float h[8], l[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) split_bf16(qt[2 * kk + u / 4][u % 4] * (scale * kLog2e), h[u], l[u]);
-            qhi[qb][kk] = v4u{pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]), pack_bf16(h[4], h[5]), pack_bf16(h[6], h[7])};
-            qlo[qb][kk] = v4u{pack_bf16(l[0], l[1]), pack_bf16(l[2], l[3]), pack_bf16(l[4], l[5]), pack_bf16(l[6], l[7])};
+                for (int u = 0; u < 8; ++u) split_bf16(qt[2 * kk + u / 4][u % 4] * (scale * kLog2e), h[u], l[u]);
+                qhi[qb][kk] = v4u{pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]), pack_bf16(h[4], h[5]), pack_bf16(h[6], h[7])};
+                qlo[qb][kk] = v4u{pack_bf16(l[0], l[1]), pack_bf16(l[2], l[3]), pack_bf16(l[4], l[5]), pack_bf16(l[6], l[7])};
+            } else {
+                float h[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    h[u] = fminf(fmaxf(qt[2 * kk + u / 4][u % 4] * (scale * kLog2e * punscale), -6.0e4f), 6.0e4f);
+                qhi[qb][kk] = v4u{pack_f16(h[0], h[1]), pack_f16(h[2], h[3]), pack_f16(h[4], h[5]), pack_f16(h[6], h[7])};
+                qlo[qb][kk] = qhi[qb][kk];
+            }
         }
     }
 
@@ -145,7 +194,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
 #pragma unroll
         for (int ib = 0; ib < RB; ++ib) z[qb][ib] = v4f{0.f, 0.f, 0.f, 0.f};
     }
-    const uint32_t one2 = 0x3f803f80u;   // two bf16 ones
+    const uint32_t one2 = PREC == 0 ? 0x3f803f80u : 0x3c003c00u;   // two ones (bf16 / fp16)
     const v4u ones = v4u{one2, one2, one2, one2};
 
     // ---- tile loader: float P -> (hi, lo) bf16, row-major and transposed ---------------
@@ -171,31 +220,42 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     };
     auto commit = [&](uint16_t* buf) __attribute__((always_inline)) {
         uint16_t* rhi = buf;
-        uint16_t* rlo = buf + kImg;
-        uint16_t* thi = buf + 2 * kImg;
-        uint16_t* tlo = thi + kImgT;
+        uint16_t* rlo = buf + (NIMG - 1) * kImg;
+        uint16_t* thi = buf + NIMG * kImg;
+        uint16_t* tlo = thi + (NIMG - 1) * kImgT;
 #pragma unroll
         for (int i = 0; i < kMaxLoads; ++i) {
             const int e = tid + i * kThreads;
             const int np = e / quads_per_row, c4 = e % quads_per_row;
             if (np < kNT / 2) {
-                float h[2][4], l[2][4];
+                if constexpr (PREC == 0) {
+                    float h[2][4], l[2][4];
 #pragma unroll
-                for (int hh = 0; hh < 2; ++hh)
+                    for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) split_bf16(stage[i][hh][c], h[hh][c], l[hh][c]);
+                        for (int c = 0; c < 4; ++c) split_bf16(stage[i][hh][c], h[hh][c], l[hh][c]);
 #pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const int nn = 2 * np + hh;
-                    *reinterpret_cast<uint2*>(rhi + nn * LDR + 4 * c4) =
-                        uint2{pack_bf16(h[hh][0], h[hh][1]), pack_bf16(h[hh][2], h[hh][3])};
-                    *reinterpret_cast<uint2*>(rlo + nn * LDR + 4 * c4) =
-                        uint2{pack_bf16(l[hh][0], l[hh][1]), pack_bf16(l[hh][2], l[hh][3])};
-                }
+                    for (int hh = 0; hh < 2; ++hh) {
+                        const int nn = 2 * np + hh;
+                        *reinterpret_cast<uint2*>(rhi + nn * LDR + 4 * c4) =
+                            uint2{pack_bf16(h[hh][0], h[hh][1]), pack_bf16(h[hh][2], h[hh][3])};
+                        *reinterpret_cast<uint2*>(rlo + nn * LDR + 4 * c4) =
+                            uint2{pack_bf16(l[hh][0], l[hh][1]), pack_bf16(l[hh][2], l[hh][3])};
+                    }
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    *reinterpret_cast<uint32_t*>(thi + (4 * c4 + c) * LDT + 2 * np) = pack_bf16(h[0][c], h[1][c]);
-                    *reinterpret_cast<uint32_t*>(tlo + (4 * c4 + c) * LDT + 2 * np) = pack_bf16(l[0][c], l[1][c]);
+                    for (int c = 0; c < 4; ++c) {
+                        *reinterpret_cast<uint32_t*>(thi + (4 * c4 + c) * LDT + 2 * np) = pack_bf16(h[0][c], h[1][c]);
+                        *reinterpret_cast<uint32_t*>(tlo + (4 * c4 + c) * LDT + 2 * np) = pack_bf16(l[0][c], l[1][c]);
+                    }
+                } else {
+                    const v4f x0 = stage[i][0] * pscale, x1 = stage[i][1] * pscale;
+                    *reinterpret_cast<uint2*>(rhi + (2 * np) * LDR + 4 * c4) =
+                        uint2{pack_f16(x0[0], x0[1]), pack_f16(x0[2], x0[3])};
+                    *reinterpret_cast<uint2*>(rhi + (2 * np + 1) * LDR + 4 * c4) =
+                        uint2{pack_f16(x1[0], x1[1]), pack_f16(x1[2], x1[3])};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        *reinterpret_cast<uint32_t*>(thi + (4 * c4 + c) * LDT + 2 * np) = pack_f16(x0[c], x1[c]);
                 }
             }
         }
@@ -211,9 +271,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         constexpr bool MASKED = decltype(masked_tag)::value;
         const uint16_t* buf = tiles + (tile & 1) * kBuf;
         const uint16_t* rhi = buf;
-        const uint16_t* rlo = buf + kImg;
-        const uint16_t* thi = buf + 2 * kImg;
-        const uint16_t* tlo = thi + kImgT;
+        const uint16_t* rlo = buf + (NIMG - 1) * kImg;
+        const uint16_t* thi = buf + NIMG * kImg;
+        const uint16_t* tlo = thi + (NIMG - 1) * kImgT;
         const bool more = tile + 1 < ntiles;
         if (more) fetch(tile + 1);
         const int n0 = tile * kNT;
@@ -232,10 +292,12 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                 const int off = (16 * nb + i16) * LDR + 32 * kk + 4 * g;
                 const uint2 h0 = *reinterpret_cast<const uint2*>(rhi + off);
                 const uint2 h1 = *reinterpret_cast<const uint2*>(rhi + off + 16);
-                const uint2 l0 = *reinterpret_cast<const uint2*>(rlo + off);
-                const uint2 l1 = *reinterpret_cast<const uint2*>(rlo + off + 16);
                 sah[nb][kk] = v4u{h0.x, h0.y, h1.x, h1.y};
-                sal[nb][kk] = v4u{l0.x, l0.y, l1.x, l1.y};
+                if constexpr (PREC == 0) {
+                    const uint2 l0 = *reinterpret_cast<const uint2*>(rlo + off);
+                    const uint2 l1 = *reinterpret_cast<const uint2*>(rlo + off + 16);
+                    sal[nb][kk] = v4u{l0.x, l0.y, l1.x, l1.y};
+                }
             }
         v4f s[kQB][kNT / 16];
         auto scores = [&](int qb) __attribute__((always_inline)) {
@@ -245,9 +307,11 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
             for (int nb = 0; nb < kNT / 16; ++nb)
 #pragma unroll
                 for (int kk = 0; kk < RB2; ++kk) {
-                    s[qb][nb] = mfma16x16x32bf16(sah[nb][kk], qhi[qb][kk], kk == 0 ? cinit : s[qb][nb]);
-                    s[qb][nb] = mfma16x16x32bf16(sal[nb][kk], qhi[qb][kk], s[qb][nb]);
-                    s[qb][nb] = mfma16x16x32bf16(sah[nb][kk], qlo[qb][kk], s[qb][nb]);
+                    s[qb][nb] = mma<PREC>(sah[nb][kk], qhi[qb][kk], kk == 0 ? cinit : s[qb][nb]);
+                    if constexpr (PREC == 0) {
+                        s[qb][nb] = mma<PREC>(sal[nb][kk], qhi[qb][kk], s[qb][nb]);
+                        s[qb][nb] = mma<PREC>(sah[nb][kk], qlo[qb][kk], s[qb][nb]);
+                    }
                 }
         };
         // Online softmax with a lazily updated reference: weights are exp2(s - mref) and may
@@ -291,11 +355,15 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                 float w[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) w[u] = __builtin_amdgcn_exp2f(s[qb][2 * kb + u / 4][u % 4]);
-                wp[qb][kb] = v4u{pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]),
-                                 pack_bf16(w[6], w[7])};
+                if constexpr (PREC == 0)
+                    wp[qb][kb] = v4u{pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]),
+                                     pack_bf16(w[6], w[7])};
+                else
+                    wp[qb][kb] = v4u{pack_f16_rtz(w[0], w[1]), pack_f16_rtz(w[2], w[3]),
+                                     pack_f16_rtz(w[4], w[5]), pack_f16_rtz(w[6], w[7])};
                 // row sums l += 1^T W^T (issued here so that the weights are produced in this
                 // stage, next to the other query block's matrix work)
-                lacc[qb] = mfma16x16x32bf16(ones, wp[qb][kb], lacc[qb]);
+                lacc[qb] = mma<PREC>(ones, wp[qb][kb], lacc[qb]);
             }
         };
         // Z(q): Z^T += P^T W^T
@@ -308,10 +376,12 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                     const int off = (16 * ib + i16) * LDT + 32 * kb + 4 * g;
                     const uint2 h0 = *reinterpret_cast<const uint2*>(thi + off);
                     const uint2 h1 = *reinterpret_cast<const uint2*>(thi + off + 16);
-                    const uint2 l0 = *reinterpret_cast<const uint2*>(tlo + off);
-                    const uint2 l1 = *reinterpret_cast<const uint2*>(tlo + off + 16);
                     zah[kb][ib] = v4u{h0.x, h0.y, h1.x, h1.y};
-                    zal[kb][ib] = v4u{l0.x, l0.y, l1.x, l1.y};
+                    if constexpr (PREC == 0) {
+                        const uint2 l0 = *reinterpret_cast<const uint2*>(tlo + off);
+                        const uint2 l1 = *reinterpret_cast<const uint2*>(tlo + off + 16);
+                        zal[kb][ib] = v4u{l0.x, l0.y, l1.x, l1.y};
+                    }
                 }
         };
         auto accumulate = [&](int qb) __attribute__((always_inline)) {
@@ -319,15 +389,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
             for (int kb = 0; kb < kNT / 32; ++kb) {
 #pragma unroll
                 for (int ib = 0; ib < RB; ++ib) {
-                    z[qb][ib] = mfma16x16x32bf16(zah[kb][ib], wp[qb][kb], z[qb][ib]);
-#ifndef SOLAR_ATTN_ZHI_ONLY
-                    z[qb][ib] = mfma16x16x32bf16(zal[kb][ib], wp[qb][kb], z[qb][ib]);
-#endif
+                    z[qb][ib] = mma<PREC>(zah[kb][ib], wp[qb][kb], z[qb][ib]);
+                    if constexpr (PREC == 0) z[qb][ib] = mma<PREC>(zal[kb][ib], wp[qb][kb], z[qb][ib]);
                 }
             }
         };
-        constexpr int kSMfma = (kNT / 16) * RB2 * 3;            // MFMAs of one S(q)
-        constexpr int kZMfma = (kNT / 32) * (2 * RB);           // MFMAs of one Z(q)
+        constexpr int kSMfma = (kNT / 16) * RB2 * (PREC == 0 ? 3 : 1);   // MFMAs of one S(q)
+        constexpr int kZMfma = (kNT / 32) * (NIMG * RB);                 // MFMAs of one Z(q)
 
         scores(0);
         reference(0);
@@ -362,7 +430,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb) {
         const float l = lacc[qb][0];
-        const float inv = l > 0.f ? 1.f / l : 0.f;
+        const float inv = l > 0.f ? punscale / l : 0.f;
 #pragma unroll
         for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= inv;
         const int m = m_wave + 16 * qb + i16;
@@ -379,37 +447,45 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     }
 }
 
-template <int D, int RB2>
-hipError_t launch_t(const void* Q, const float* V, const float* P, const int32_t* lengths, int B,
-                    int N, int r, int M, float scale, bool bf16, float* O, hipStream_t stream) {
+template <int D, int RB2, int PREC>
+hipError_t launch_t(const void* Q, const float* S, const float* V, const float* P,
+                    const int32_t* lengths, int B, int N, int r, int M, float scale, float* O,
+                    hipStream_t stream) {
     constexpr int RP = 32 * RB2;
+    constexpr int NIMG = PREC == 0 ? 2 : 1;
     const size_t lds = sizeof(float) * (size_t)D * (RP + 4) +
-                       sizeof(uint16_t) * 2 * (2 * (size_t)kNT * (RP + SOLAR_ATTN_RPAD) + 2 * (size_t)RP * (kNT + 12));
+                       sizeof(uint16_t) * 2 * NIMG *
+                           ((size_t)kNT * (RP + SOLAR_ATTN_RPAD) + (size_t)RP * (kNT + 12));
     dim3 grid(ceil_div(M, kWaves * kQB * 16) * 8 * ceil_div(B, 8)), block(kThreads);
-    if (bf16) {
-        auto kern = attention_seq_bf16_kernel<D, RB2, true>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
-    } else {
-        auto kern = attention_seq_bf16_kernel<D, RB2, false>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
-    }
+    auto kern = attention_seq_bf16_kernel<D, RB2, true, PREC>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, P, lengths, B, N, r, M, scale, O);
     return hipGetLastError();
 }
 
-template <int D>
-hipError_t launch_d(const void* Q, const float* V, const float* P, const int32_t* lengths, int B,
-                    int N, int r, int M, float scale, bool bf16, float* O, hipStream_t stream) {
-    if (r <= 32) return launch_t<D, 1>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+template <int D, int PREC>
+hipError_t launch_d(const void* Q, const float* S, const float* V, const float* P,
+                    const int32_t* lengths, int B, int N, int r, int M, float scale, float* O,
+                    hipStream_t stream) {
+    if (r <= 32) return launch_t<D, 1, PREC>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
     if constexpr (D < 256) {
-        if (r <= 64) return launch_t<D, 2>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        if (r <= 64) return launch_t<D, 2, PREC>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
     }
     return hipErrorInvalidValue;
+}
+
+template <int PREC>
+hipError_t launch_p(const void* Q, const float* S, const float* V, const float* P,
+                    const int32_t* lengths, int B, int N, int d, int r, int M, float scale, float* O,
+                    hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_d<64, PREC>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 128: return launch_d<128, PREC>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 256: return launch_d<256, PREC>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
@@ -418,15 +494,13 @@ bool attention_seq_bf16_supported(int d, int r) {
     return (d == 64 || d == 128 || d == 256) && r >= 4 && r <= (d == 256 ? 32 : 64) && (r % 4) == 0;
 }
 
-hipError_t launch_attention_seq_bf16(const void* Q, const float* V, const float* P,
+// Q is bf16.  split == true: bf16 head + tail operands (about 16 mantissa bits in the scores);
+// split == false: single fp16 operands scaled by S[.][0] (S must not be null).
+hipError_t launch_attention_seq_bf16(const void* Q, const float* S, const float* V, const float* P,
                                      const int32_t* lengths, int B, int N, int d, int r, int M,
-                                     float scale, bool bf16, float* O, hipStream_t stream) {
-    switch (d) {
-        case 64: return launch_d<64>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
-        case 128: return launch_d<128>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
-        case 256: return launch_d<256>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
-        default: return hipErrorInvalidValue;
-    }
+                                     float scale, bool split, float* O, hipStream_t stream) {
+    if (split || !S) return launch_p<0>(Q, S, V, P, lengths, B, N, d, r, M, scale, O, stream);
+    return launch_p<1>(Q, S, V, P, lengths, B, N, d, r, M, scale, O, stream);
 }
 
 }  // namespace solar

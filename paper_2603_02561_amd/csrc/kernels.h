@@ -42,9 +42,9 @@ hipError_t launch_attention_tokens(const void* Q, const float* S, const float* V
 
 // attention_bf16.hip
 bool attention_seq_bf16_supported(int d, int r);
-hipError_t launch_attention_seq_bf16(const void* Q, const float* V, const float* P,
+hipError_t launch_attention_seq_bf16(const void* Q, const float* S, const float* V, const float* P,
                                      const int32_t* lengths, int B, int N, int d, int r, int M,
-                                     float scale, bool bf16, float* O, hipStream_t stream);
+                                     float scale, bool split, float* O, hipStream_t stream);
 
 // dense_ref.hip
 hipError_t launch_dense_ref(const void* Q, const void* X, const int32_t* lengths, int B, int N,
