@@ -44,7 +44,7 @@ namespace {
 #define SOLAR_ATTN_THREADS 512
 #endif
 #ifndef SOLAR_ATTN_NT
-#define SOLAR_ATTN_NT 64
+#define SOLAR_ATTN_NT 128
 #endif
 constexpr int kThreads = SOLAR_ATTN_THREADS;
 constexpr int kWaves = kThreads / 64;
