@@ -63,6 +63,7 @@ EigParams eig_params_from_env() {
     if (const char* s = std::getenv("SOLAR_EIG_SWEEPS")) p.sweeps = std::atoi(s);
     if (const char* s = std::getenv("SOLAR_EIG_MAXIT")) p.max_iter = std::atoi(s);
     if (const char* s = std::getenv("SOLAR_EIG_DEBUG")) p.debug_counts = std::atoi(s);
+    if (const char* s = std::getenv("SOLAR_EIG_MGS")) p.mgs_steps = std::atoi(s);
     return p;
 }
 

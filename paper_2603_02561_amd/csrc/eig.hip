@@ -177,6 +177,67 @@ __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
     return offmax;
 }
 
+// One pass of modified Gram-Schmidt over the L columns of Zc, then normalization into Qc:
+// a cheap orthonormal basis of span(Z) for the early power steps, where only the span
+// matters.  Step j projects column j out of every later column (one team of TM lanes per
+// later column; the team also recomputes |z_j|^2, so a step needs a single barrier).
+// Columns that collapse below dead2 (squared norm) are dropped.  The basis is orthonormal
+// to about 2^-24 * cond(Z), which is all a power step needs.
+template <int D, int L>
+__device__ __forceinline__ void mgs_orthonormalize(float* Zc, float* Qc, float dead2) {
+    constexpr int LD = D + 4;
+    constexpr int TM = min_c(16, D / 4);         // lanes per column
+    constexpr int CH = D / (4 * TM);
+    constexpr int NTEAM = kEigThreads / TM;
+    const int tid = threadIdx.x;
+    const int team = tid / TM, u = tid % TM;
+#pragma unroll 1
+    for (int j = 0; j < L - 1; ++j) {
+        const float* zj = Zc + j * LD + 4 * u;
+        v4f a[CH];
+#pragma unroll
+        for (int k = 0; k < CH; ++k) a[k] = *reinterpret_cast<const v4f*>(zj + 4 * TM * k);
+        float njj = 0.f;
+#pragma unroll
+        for (int k = 0; k < CH; ++k) njj += a[k].x * a[k].x + a[k].y * a[k].y + a[k].z * a[k].z + a[k].w * a[k].w;
+        njj = team_sum<TM>(njj);
+        if (njj > dead2) {
+            const float inv = 1.f / njj;
+            for (int c = j + 1 + team; c < L; c += NTEAM) {
+                float* zc = Zc + c * LD + 4 * u;
+                v4f b[CH];
+                float g = 0.f;
+#pragma unroll
+                for (int k = 0; k < CH; ++k) {
+                    b[k] = *reinterpret_cast<const v4f*>(zc + 4 * TM * k);
+                    g += a[k].x * b[k].x + a[k].y * b[k].y + a[k].z * b[k].z + a[k].w * b[k].w;
+                }
+                g = team_sum<TM>(g) * inv;
+#pragma unroll
+                for (int k = 0; k < CH; ++k) *reinterpret_cast<v4f*>(zc + 4 * TM * k) = b[k] - g * a[k];
+            }
+        }
+        __syncthreads();
+    }
+    // normalize (dead columns become zero)
+    for (int c = team; c < L; c += NTEAM) {
+        const float* zc = Zc + c * LD + 4 * u;
+        float* qc = Qc + c * LD + 4 * u;
+        v4f b[CH];
+        float nn = 0.f;
+#pragma unroll
+        for (int k = 0; k < CH; ++k) {
+            b[k] = *reinterpret_cast<const v4f*>(zc + 4 * TM * k);
+            nn += b[k].x * b[k].x + b[k].y * b[k].y + b[k].z * b[k].z + b[k].w * b[k].w;
+        }
+        nn = team_sum<TM>(nn);
+        const float inv = nn > dead2 ? __builtin_amdgcn_rsqf(nn) : 0.f;
+#pragma unroll
+        for (int k = 0; k < CH; ++k) *reinterpret_cast<v4f*>(qc + 4 * TM * k) = b[k] * inv;
+    }
+    __syncthreads();
+}
+
 template <int D, int L>
 __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     const float* __restrict__ G, const int32_t* __restrict__ lengths, int N, int r,
@@ -214,11 +275,18 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     __syncthreads();
 
     const int col = tid / TC, cu = tid % TC;
+    // The iteration alternates cheap and full steps.  After a power step Z = G Q the block is
+    // re-orthonormalized either by one Gram-Schmidt pass (`mgs_steps` times in a row: only the
+    // span matters then) or by the Jacobi phase, which also rotates the basis to Ritz vectors;
+    // the step after a Jacobi phase checks the residuals of those Ritz pairs.
     bool orth_ok = false;
     float prev_res = 3.0e38f;
     int it = 0;
     int status = 0;
     int total_sweeps = 0;
+    bool have_ritz = false;
+    int cheap_left = prm.mgs_steps;
+    int cycle = 0;
     long long cyc_gemm = 0, cyc_jac = 0;
     const long long wall0 = wall_clock64();
     const long long cyc0 = clock64();
@@ -246,7 +314,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
         }
         __syncthreads();
         const float dead2 = kDeadRel * kDeadRel * __int_as_float(sh_bits2);
-        if (it > 0) {
+        if (have_ritz) {
             if (tid < L) {
                 const float th = theta[tid];
                 int rk = 0;
@@ -270,6 +338,16 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
         }
         __syncthreads();
         if (tid == 0) { sh_bits = 0; sh_bits2 = 0; }
+        if (cheap_left > 0) {
+            --cheap_left;
+            have_ritz = false;
+            mgs_orthonormalize<D, L>(Zc, Qc, dead2);
+            continue;
+        }
+        // a failed check means slow convergence: spend more cheap steps before the next one
+        ++cycle;
+        cheap_left = prm.mgs_steps << (cycle < 3 ? cycle : 3);
+        have_ritz = true;
         // orthogonalize the columns of Z (this also rotates them towards Ritz vectors)
         orth_ok = false;
         t0 = clock64();
@@ -376,6 +454,7 @@ EigParams eig_default_params() {
     p.tol_orth = 2.0e-6f;
     p.max_iter = 40;
     p.sweeps = 12;
+    p.mgs_steps = 2;
     p.debug_counts = 0;
     return p;
 }

@@ -19,6 +19,7 @@ struct EigParams {
     float tol_orth;     // a sweep whose largest |cos| is below this ends the Jacobi phase
     int max_iter;       // cap on power steps
     int sweeps;         // cap on Jacobi sweeps per power step
+    int mgs_steps;      // leading power steps that use a Gram-Schmidt pass instead of Jacobi
     int debug_counts;   // nonzero: info[] returns 1000*power_steps + sweeps instead of status
 };
 EigParams eig_default_params();
