@@ -210,3 +210,49 @@ def test_argument_errors(lib):
     assert rc == 0
     assert db.info.cpu().tolist() == [0, -1]
     assert float(db.S[1].abs().max()) == 0.0 and float(db.V[1].abs().max()) == 0.0
+
+
+EDGE = [
+    # name, B, N, d, r, M, dtype, lengths
+    ("tiny_N_single_query", 1, 17, 64, 4, 1, synth.F32, None),
+    ("len_equals_r", 3, 40, 64, 8, 5, synth.F32, [8, 40, 9]),
+    ("nine_users_bf16", 9, 130, 128, 16, 17, synth.BF16, None),
+    ("one_row_tail_tile", 2, 129, 128, 32, 257, synth.BF16, [129, 65]),
+    ("r_is_d", 1, 200, 64, 64, 20, synth.F32, None),
+]
+
+
+@pytest.mark.parametrize("name,B,N,d,r,M,dtype,lengths", EDGE, ids=[e[0] for e in EDGE])
+def test_edge_shapes(lib, oracle, name, B, N, d, r, M, dtype, lengths):
+    """Degenerate and ragged shapes: fewer rows than a tile, a single candidate, a valid length
+    equal to the rank, a batch that does not fill the 8-way workgroup ordering, a one-row last
+    tile, and r = d (no truncation: SVD-Attention is dense attention for any X)."""
+    import torch
+    print(f"[case] edge {name}", flush=True)
+    kind = "gauss_lowrank" if name != "r_is_d" else "spectrum"
+    w = synth.make_workload("edge", B, N, d, min(r, 16) if kind == "gauss_lowrank" else r, M, dtype, kind,
+                            1.0, 0.0, seed=900 + len(name))
+    w.r = r
+    if lengths is not None:
+        w.lengths = np.asarray(lengths, dtype=np.int32)
+    if name == "r_is_d":
+        rng = np.random.default_rng(5)
+        w.X = rng.standard_normal(w.X.shape).astype(np.float32)   # full rank, no structure
+    db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, dtype == synth.BF16)
+    db.factorize()
+    torch.cuda.synchronize()
+    assert np.all(db.info.cpu().numpy() == 0)
+    f = oracle.svd_factorize(w.X, w.r, w.lengths)
+    tol = TOL[dtype]
+    for scale in (1.0, 4.0):
+        db.attention(scale, 0)
+        torch.cuda.synchronize()
+        want = oracle.svd_attention(w.Q, w.X, f["S"], f["V"], scale, 0, w.lengths)
+        err = rel_err(db.O.cpu().numpy(), want)
+        dense = oracle.dense_attention(w.Q, w.X, scale, w.lengths)
+        print(f"  mode0 scale={scale} err {err:.3e}  (oracle mode0 vs dense {rel_err(want, dense):.1e})", flush=True)
+        assert err < tol
+        if name == "r_is_d":
+            assert rel_err(db.O.cpu().numpy(), dense) < tol
+    s_err = np.abs(db.S.cpu().numpy() - f["S"]).max() / f["S"].max()
+    assert s_err < (1e-4 if dtype == synth.F32 else 1e-3)
