@@ -16,6 +16,8 @@
 // per-chunk partial blocks go to the workspace, and gram_finalize_kernel adds them
 // in a fixed order and undoes the fragment permutation.  Results are therefore
 // bitwise reproducible.
+#include <cstdlib>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -25,6 +27,9 @@ template <int CPL>
 __host__ __device__ constexpr int gram_pairs() { return CPL * (CPL + 1) / 2; }
 
 constexpr int kGramWaves = 4;
+#ifndef SOLAR_GRAM_RING
+#define SOLAR_GRAM_RING 3
+#endif
 
 template <int CPL, bool BF16>
 __global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
@@ -51,49 +56,49 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
     if constexpr (BF16) {
         constexpr int W = CPL / 2;  // 32-bit words per lane per row
         const uint32_t* X = reinterpret_cast<const uint32_t*>(Xv) + (size_t)b * N * (D / 2);
-        uint32_t cur[8][W], nxt[8][W];
-        auto load = [&](uint32_t (&dst)[8][W], int base) {
+        auto load_row = [&](uint32_t (&dst)[W], const uint32_t* p) __attribute__((always_inline)) {
+            if constexpr (W == 2) {
+                uint2 v = *reinterpret_cast<const uint2*>(p);
+                dst[0] = v.x; dst[1] = v.y;
+            } else {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const int row = base + 8 * h + t;
-                if (row < r1) {
-                    const uint32_t* p = X + (size_t)row * (D / 2) + W * j;
-                    if constexpr (W == 4) {
-                        v4u v = *reinterpret_cast<const v4u*>(p);
-                        dst[t][0] = v.x; dst[t][1] = v.y; dst[t][2] = v.z; dst[t][3] = v.w;
-                    } else if constexpr (W == 2) {
-                        uint2 v = *reinterpret_cast<const uint2*>(p);
-                        dst[t][0] = v.x; dst[t][1] = v.y;
-                    } else {
-#pragma unroll
-                        for (int q = 0; q < W / 4; ++q) {
-                            v4u v = *reinterpret_cast<const v4u*>(p + 4 * q);
-                            dst[t][4 * q + 0] = v.x; dst[t][4 * q + 1] = v.y;
-                            dst[t][4 * q + 2] = v.z; dst[t][4 * q + 3] = v.w;
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int w = 0; w < W; ++w) dst[t][w] = 0u;
+                for (int q = 0; q < W / 4; ++q) {
+                    v4u v = *reinterpret_cast<const v4u*>(p + 4 * q);
+                    dst[4 * q + 0] = v.x; dst[4 * q + 1] = v.y;
+                    dst[4 * q + 2] = v.z; dst[4 * q + 3] = v.w;
                 }
             }
         };
-        int base = r0 + wave * STEP;
-        if (base < r1) load(cur, base);
-        while (base < r1) {
-            const int nbase = base + kGramWaves * STEP;
-            if (nbase < r1) load(nxt, nbase);
+        // a step whose 32 rows are all valid issues its eight loads back to back; only the
+        // ragged last step of a chunk pays for per-row predicates
+        auto load = [&](uint32_t (&dst)[8][W], int base) __attribute__((always_inline)) {
+            const uint32_t* p0 = X + (size_t)(base + 8 * h) * (D / 2) + W * j;
+            if (base + STEP <= r1) {
+#pragma unroll
+                for (int t = 0; t < 8; ++t) load_row(dst[t], p0 + (size_t)t * (D / 2));
+            } else {
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const bool ok = base + 8 * h + t < r1;
+                    load_row(dst[t], ok ? p0 + (size_t)t * (D / 2) : X);
+                    if (!ok) {
+#pragma unroll
+                        for (int w = 0; w < W; ++w) dst[t][w] = 0u;
+                    }
+                }
+            }
+        };
+        auto compute = [&](const uint32_t (&src)[8][W]) __attribute__((always_inline)) {
             // 8x(2W) transpose of 16-bit elements: fragment s holds column CPL*j+s of the
-            // lane's eight rows, two rows per word.
+            // lane's eight rows, two rows per word (one byte-permute per word).
             v4u frag[CPL];
 #pragma unroll
             for (int s = 0; s < CPL; ++s) {
                 uint32_t o[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint32_t a = cur[2 * u][s / 2], c = cur[2 * u + 1][s / 2];
-                    o[u] = (s & 1) ? ((a >> 16) | (c & 0xffff0000u)) : ((a & 0xffffu) | (c << 16));
-                }
+                for (int u = 0; u < 4; ++u)
+                    o[u] = __builtin_amdgcn_perm(src[2 * u + 1][s / 2], src[2 * u][s / 2],
+                                                 (s & 1) ? 0x07060302u : 0x05040100u);
                 frag[s] = v4u{o[0], o[1], o[2], o[3]};
             }
             int p = 0;
@@ -104,13 +109,28 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
                     acc[p] = mfma16x16x32bf16(frag[s1], frag[s2], acc[p]);
                     ++p;
                 }
-            if (nbase < r1) {
+        };
+        // ring of kRing row blocks per wave: kRing-1 blocks of loads stay in flight while one
+        // block is multiplied, with the ring index fixed at compile time by the unrolling
+        constexpr int kRing = SOLAR_GRAM_RING;
+        uint32_t ring[kRing][8][W];
+        constexpr int stride = kGramWaves * STEP;
+        int base = r0 + wave * STEP;
 #pragma unroll
-                for (int t = 0; t < 8; ++t)
+        for (int k = 0; k < kRing - 1; ++k)
+            if (base + k * stride < r1) load(ring[k], base + k * stride);
+        bool more = base < r1;
+        while (more) {
 #pragma unroll
-                    for (int w = 0; w < W; ++w) cur[t][w] = nxt[t][w];
+            for (int k = 0; k < kRing; ++k) {
+                if (more) {
+                    const int ahead = base + (kRing - 1) * stride;
+                    if (ahead < r1) load(ring[(k + kRing - 1) % kRing], ahead);
+                    compute(ring[k]);
+                    base += stride;
+                    more = base < r1;
+                }
             }
-            base = nbase;
         }
     } else {
         const float* X = reinterpret_cast<const float*>(Xv) + (size_t)b * N * D;
@@ -195,6 +215,7 @@ __global__ __launch_bounds__(256) void gram_finalize_kernel(const float* __restr
     const int off = pair * 256 + (i2 + 16 * (i1 / 4)) * 4 + (i1 % 4);
     const float* p = partials + (size_t)b * nsplit * (NP * 256) + off;
     float acc = 0.f;
+#pragma unroll 8
     for (int s = 0; s < nsplit; ++s) acc += p[(size_t)s * (NP * 256)];
     G[(size_t)b * D * D + e] = acc;
 }
@@ -353,8 +374,15 @@ __global__ __launch_bounds__(256) void gram256_finalize_kernel(const float* __re
 }
 
 int gram_nsplit(int B, int N) {
-    // Aim at about two workgroups per compute unit, at least 512 rows per chunk.
-    int want = ceil_div(512, B);
+    // One workgroup per compute unit (its accumulators leave room for one wave per SIMD, so a
+    // second round of workgroups would only queue behind the first), at least 512 rows per
+    // chunk.  SOLAR_GRAM_WGS overrides the target count for tuning.
+    static const int target = [] {
+        const char* e = std::getenv("SOLAR_GRAM_WGS");
+        const int v = e ? std::atoi(e) : 0;
+        return v > 0 ? v : 256;
+    }();
+    int want = ceil_div(target, B);
     int cap = ceil_div(N, 512);
     int n = want < cap ? want : cap;
     if (n < 1) n = 1;
