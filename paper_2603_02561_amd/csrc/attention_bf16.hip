@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     const float* __restrict__ P, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
     float scale, float* __restrict__ O) {
     constexpr int NIMG = PREC == 0 ? 2 : 1;   // images per layout: head (+ tail)
-    constexpr float kJump = PREC == 0 ? 16.f : 8.f;   // log2 units a tile maximum may exceed the reference by
+    constexpr float kBig = PREC == 0 ? 65536.f : 1024.f;   // a tile row sum above this moves the reference
     constexpr int RP = 32 * RB2;          // padded rank
     constexpr int RB = RP / 16;
     constexpr int LDV = RP + 4;           // floats
@@ -313,12 +313,6 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                         s[qb][nb] = mma<PREC>(sah[nb][kk], qlo[qb][kk], s[qb][nb]);
                     }
                 }
-        };
-        // Online softmax with a lazily updated reference: weights are exp2(s - mref) and may
-        // exceed one; mref only moves (and Z, l are rescaled) when a tile's maximum exceeds it
-        // by more than kJump, or on the first tile.  exp2(kJump) times the sequence length is
-        // far inside the float range, so nothing can overflow.
-        auto reference = [&](int qb) __attribute__((always_inline)) {
             // mask rows past the valid length (register t of block nb is row 16*nb + 4*g + t)
             if constexpr (MASKED) {
 #pragma unroll
@@ -327,29 +321,14 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                     for (int t = 0; t < 4; ++t)
                         if (n0 + 16 * nb + 4 * g + t >= len) s[qb][nb][t] = -INFINITY;
             }
-            float v = -INFINITY;
-#pragma unroll
-            for (int nb = 0; nb < kNT / 16; ++nb)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) v = fmaxf(v, s[qb][nb][t]);
-            v = wave_xor_max(v, 16);
-            v = wave_xor_max(v, 32);   // tile maximum relative to mref; finite: a tile has a valid row
-            const bool first = mref[qb] == -INFINITY;
-            if (__any(first || v > kJump)) {   // uniform over the wave, rare
-                const float shift = (first || v > kJump) ? v : 0.f;
-                const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-shift);
-                mref[qb] = (first ? 0.f : mref[qb]) + shift;
-#pragma unroll
-                for (int nb = 0; nb < kNT / 16; ++nb) s[qb][nb] -= shift;
-                lacc[qb] *= alpha;
-#pragma unroll
-                for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= alpha;
-            }
         };
-        // weights rounded to bf16 and packed as the B operand of the next product: slot
-        // (g, u) of chunk kb is row 32*kb + 16*(u/4) + 4*g + u%4
+        // weights rounded to 16 bits and packed as the B operand of the next product: slot
+        // (g, u) of chunk kb is row 32*kb + 16*(u/4) + 4*g + u%4.  lsum receives lacc plus the
+        // row sums 1^T W^T of the rounded weights (one MFMA against a tile of ones per chunk).
         v4u wp[kQB][kNT / 32];
-        auto weights = [&](int qb) __attribute__((always_inline)) {
+        v4f lsum[kQB];
+        auto weights = [&](int qb, v4f lstart) __attribute__((always_inline)) {
+            lsum[qb] = lstart;
 #pragma unroll
             for (int kb = 0; kb < kNT / 32; ++kb) {
                 float w[8];
@@ -361,10 +340,38 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                 else
                     wp[qb][kb] = v4u{pack_f16_rtz(w[0], w[1]), pack_f16_rtz(w[2], w[3]),
                                      pack_f16_rtz(w[4], w[5]), pack_f16_rtz(w[6], w[7])};
-                // row sums l += 1^T W^T (issued here so that the weights are produced in this
-                // stage, next to the other query block's matrix work)
-                lacc[qb] = mma<PREC>(ones, wp[qb][kb], lacc[qb]);
+                lsum[qb] = mma<PREC>(ones, wp[qb][kb], lsum[qb]);
             }
+        };
+        // Online softmax with a lazily updated reference: weights are exp2(s - mref) and may
+        // exceed one.  No maximum is taken on the common path: a weight above kBig shows in the
+        // tile's row sum, which the matrix unit delivers anyway, so the row sum is what is
+        // tested.  Only when it exceeds kBig (or is not finite), or on the first tile, is the
+        // tile maximum formed, mref moved there, Z and l rescaled and the weights recomputed.
+        // Every accepted weight is below kBig, far inside the range of the 16-bit formats, and
+        // kBig times the sequence length is far inside the float range.
+        auto settle = [&](int qb) __attribute__((always_inline)) {
+            const bool first = mref[qb] == -INFINITY;
+            const bool big = !(lsum[qb][0] - lacc[qb][0] <= kBig);
+            if (__any(first || big)) {   // uniform over the wave, rare
+                float v = -INFINITY;
+#pragma unroll
+                for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) v = fmaxf(v, s[qb][nb][t]);
+                v = wave_xor_max(v, 16);
+                v = wave_xor_max(v, 32);   // tile maximum relative to mref; finite: a tile has a valid row
+                const float shift = (first || big) ? v : 0.f;
+                const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-shift);
+                mref[qb] = (first ? 0.f : mref[qb]) + shift;
+#pragma unroll
+                for (int nb = 0; nb < kNT / 16; ++nb) s[qb][nb] -= shift;
+                lacc[qb] *= alpha;
+#pragma unroll
+                for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= alpha;
+                weights(qb, lacc[qb]);
+            }
+            lacc[qb] = lsum[qb];
         };
         // Z(q): Z^T += P^T W^T
         v4u zah[kNT / 32][RB], zal[kNT / 32][RB];
@@ -398,25 +405,25 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         constexpr int kZMfma = (kNT / 32) * (NIMG * RB);                 // MFMAs of one Z(q)
 
         scores(0);
-        reference(0);
         // S(1) on the matrix unit under exp(0) on the vector ALU
         scores(1);
         load_zops();
-        weights(0);
+        weights(0, lacc[0]);
 #pragma unroll
         for (int i = 0; i < kSMfma; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
             __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // two VALU
         }
-        reference(1);
+        settle(0);
         // Z(0) under exp(1)
         accumulate(0);
-        weights(1);
+        weights(1, lacc[1]);
 #pragma unroll
         for (int i = 0; i < kZMfma; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
         }
+        settle(1);
         // Z(1) under the split of the next tile
         accumulate(1);
         if (more) commit(tiles + ((tile + 1) & 1) * kBuf);
