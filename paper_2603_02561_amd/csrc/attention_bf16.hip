@@ -49,7 +49,10 @@ namespace {
 constexpr int kThreads = SOLAR_ATTN_THREADS;
 constexpr int kWaves = kThreads / 64;
 constexpr int kQB = 2;    // 16-query blocks per wave
-constexpr int kNT = SOLAR_ATTN_NT;   // rows of P per tile
+// rows of P per tile; the split variant (two images per layout) and ranks above 32 take half the
+// rows so that three tile buffers fit the LDS and the operands fit the registers
+template <int PREC, int RB2>
+constexpr int tile_rows() { return (PREC == 0 || RB2 > 1) ? 64 : SOLAR_ATTN_NT; }
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -85,10 +88,18 @@ __device__ __forceinline__ uint32_t pack_f16_rtz(float a, float b) {
 }
 
 template <int PREC>
+__device__ __forceinline__ uint32_t pack_w(float a, float b);
+
+template <int PREC>
 __device__ __forceinline__ v4f mma(v4u a, v4u b, v4f c) {
     if constexpr (PREC == 0) return mfma16x16x32bf16(a, b, c);
     else return mfma16x16x32f16(a, b, c);
 }
+
+template <>
+__device__ __forceinline__ uint32_t pack_w<0>(float a, float b) { return pack_bf16(a, b); }
+template <>
+__device__ __forceinline__ uint32_t pack_w<1>(float a, float b) { return pack_f16_rtz(a, b); }
 
 template <int D, int RB2, bool BF16, int PREC>
 __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
@@ -96,6 +107,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     const float* __restrict__ P, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
     float scale, float* __restrict__ O) {
     constexpr int NIMG = PREC == 0 ? 2 : 1;   // images per layout: head (+ tail)
+    constexpr int kNT = tile_rows<PREC, RB2>();
     constexpr float kBig = PREC == 0 ? 65536.f : 1024.f;   // a tile row sum above this moves the reference
     constexpr int RP = 32 * RB2;          // padded rank
     constexpr int RB = RP / 16;
@@ -110,7 +122,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     constexpr int kBuf = NIMG * (kImg + kImgT);  // row-major head (, tail); transposed head (, tail)
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                                             // [D][LDV]
-    uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);  // [2][kBuf]
+    uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);  // [3][kBuf]
     // Workgroups are dealt to the 8 XCDs round-robin by linear id.  All M-tiles of a user
     // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
     const int mtiles = ceil_div(M, kWaves * kQB * 16);
@@ -133,8 +145,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         const int k = e / RP, c = e % RP;
         Vs[k * LDV + c] = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
     }
-    // zero both tile buffers once: padded rank columns / rows stay zero for ever
-    for (int e = tid; e < 2 * kBuf / 2; e += kThreads) reinterpret_cast<uint32_t*>(tiles)[e] = 0u;
+    // zero the tile buffers once: padded rank columns / rows stay zero for ever
+    for (int e = tid; e < 3 * kBuf / 2; e += kThreads) reinterpret_cast<uint32_t*>(tiles)[e] = 0u;
     __syncthreads();
 
     // ---- prologue: Qt^T = V^T Q^T in float, scaled by scale*log2(e), split hi/lo ------
@@ -261,30 +273,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         }
     };
 
-    const int ntiles = ceil_div(len, kNT);
-    if (ntiles > 0) { fetch(0); commit(tiles); }
-    __syncthreads();
-
-    // One tile of the sequence.  MASKED is only instantiated for the ragged last tile, so the
-    // full tiles carry no per-score select.
-    auto do_tile = [&](int tile, auto masked_tag) __attribute__((always_inline)) {
-        constexpr bool MASKED = decltype(masked_tag)::value;
-        const uint16_t* buf = tiles + (tile & 1) * kBuf;
+    // ---- per-tile building blocks -------------------------------------------------------
+    // A operands of the score product: 16 rows of P per block, slot (g, u) = rank
+    // 32*kk + 16*(u/4) + 4*g + u%4 (row-major image).
+    v4u sah[kNT / 16][RB2], sal[kNT / 16][RB2];
+    auto load_sops = [&](const uint16_t* buf) __attribute__((always_inline)) {
         const uint16_t* rhi = buf;
         const uint16_t* rlo = buf + (NIMG - 1) * kImg;
-        const uint16_t* thi = buf + NIMG * kImg;
-        const uint16_t* tlo = thi + (NIMG - 1) * kImgT;
-        const bool more = tile + 1 < ntiles;
-        if (more) fetch(tile + 1);
-        const int n0 = tile * kNT;
-
-        // The work of a tile is staged so that the matrix unit and the vector ALU of the
-        // wave run side by side on different query blocks:
-        //   S(0) | S(1) + exp(0) | Z(0) + exp(1) | Z(1) + split of the next tile
-        // S(q): scores of query block q relative to its reference value: the accumulators
-        //       start at -mref (first tile: 0), so what leaves the matrix unit is s - mref.
-        //       A = 16 rows of P, slot (g, u) = rank 32*kk + 16*(u/4) + 4*g + u%4.
-        v4u sah[kNT / 16][RB2], sal[kNT / 16][RB2];
 #pragma unroll
         for (int nb = 0; nb < kNT / 16; ++nb)
 #pragma unroll
@@ -299,139 +294,255 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                     sal[nb][kk] = v4u{l0.x, l0.y, l1.x, l1.y};
                 }
             }
-        v4f s[kQB][kNT / 16];
-        auto scores = [&](int qb) __attribute__((always_inline)) {
-            const float c0 = (mref[qb] == -INFINITY) ? 0.f : -mref[qb];
-            const v4f cinit = v4f{c0, c0, c0, c0};
+    };
+    // A operands of Z^T += P^T W^T: 16 ranks per block, 32 rows of the tile per chunk
+    // (transposed image).
+    v4u zah[kNT / 32][RB], zal[kNT / 32][RB];
+    auto load_zops = [&](const uint16_t* buf) __attribute__((always_inline)) {
+        const uint16_t* thi = buf + NIMG * kImg;
+        const uint16_t* tlo = thi + (NIMG - 1) * kImgT;
+#pragma unroll
+        for (int kb = 0; kb < kNT / 32; ++kb)
+#pragma unroll
+            for (int ib = 0; ib < RB; ++ib) {
+                const int off = (16 * ib + i16) * LDT + 32 * kb + 4 * g;
+                const uint2 h0 = *reinterpret_cast<const uint2*>(thi + off);
+                const uint2 h1 = *reinterpret_cast<const uint2*>(thi + off + 16);
+                zah[kb][ib] = v4u{h0.x, h0.y, h1.x, h1.y};
+                if constexpr (PREC == 0) {
+                    const uint2 l0 = *reinterpret_cast<const uint2*>(tlo + off);
+                    const uint2 l1 = *reinterpret_cast<const uint2*>(tlo + off + 16);
+                    zal[kb][ib] = v4u{l0.x, l0.y, l1.x, l1.y};
+                }
+            }
+    };
+    // S(q): scores of query block q relative to its reference value: the accumulators start at
+    // -mref (before the first tile: 0), so what leaves the matrix unit is s - mref.  The masked
+    // form, which sets rows past the valid length to -inf, is only instantiated for a ragged
+    // last tile (register t of block nb is row 16*nb + 4*g + t).
+    v4f s[kQB][kNT / 16];
+    auto scores = [&](int qb, int n0, auto masked_tag) __attribute__((always_inline)) {
+        const float c0 = (mref[qb] == -INFINITY) ? 0.f : -mref[qb];
+        const v4f cinit = v4f{c0, c0, c0, c0};
+#pragma unroll
+        for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+            for (int kk = 0; kk < RB2; ++kk) {
+                s[qb][nb] = mma<PREC>(sah[nb][kk], qhi[qb][kk], kk == 0 ? cinit : s[qb][nb]);
+                if constexpr (PREC == 0) {
+                    s[qb][nb] = mma<PREC>(sal[nb][kk], qhi[qb][kk], s[qb][nb]);
+                    s[qb][nb] = mma<PREC>(sah[nb][kk], qlo[qb][kk], s[qb][nb]);
+                }
+            }
+        if constexpr (decltype(masked_tag)::value) {
 #pragma unroll
             for (int nb = 0; nb < kNT / 16; ++nb)
 #pragma unroll
-                for (int kk = 0; kk < RB2; ++kk) {
-                    s[qb][nb] = mma<PREC>(sah[nb][kk], qhi[qb][kk], kk == 0 ? cinit : s[qb][nb]);
-                    if constexpr (PREC == 0) {
-                        s[qb][nb] = mma<PREC>(sal[nb][kk], qhi[qb][kk], s[qb][nb]);
-                        s[qb][nb] = mma<PREC>(sah[nb][kk], qlo[qb][kk], s[qb][nb]);
-                    }
-                }
-            // mask rows past the valid length (register t of block nb is row 16*nb + 4*g + t)
-            if constexpr (MASKED) {
+                for (int t = 0; t < 4; ++t)
+                    if (n0 + 16 * nb + 4 * g + t >= len) s[qb][nb][t] = -INFINITY;
+        }
+    };
+    // one 16-row block of S(q)
+    auto score_block = [&](int qb, int nb, int n0, auto masked_tag) __attribute__((always_inline)) {
+        const float c0 = (mref[qb] == -INFINITY) ? 0.f : -mref[qb];
+        const v4f cinit = v4f{c0, c0, c0, c0};
 #pragma unroll
-                for (int nb = 0; nb < kNT / 16; ++nb)
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        if (n0 + 16 * nb + 4 * g + t >= len) s[qb][nb][t] = -INFINITY;
+        for (int kk = 0; kk < RB2; ++kk) {
+            s[qb][nb] = mma<PREC>(sah[nb][kk], qhi[qb][kk], kk == 0 ? cinit : s[qb][nb]);
+            if constexpr (PREC == 0) {
+                s[qb][nb] = mma<PREC>(sal[nb][kk], qhi[qb][kk], s[qb][nb]);
+                s[qb][nb] = mma<PREC>(sah[nb][kk], qlo[qb][kk], s[qb][nb]);
             }
-        };
-        // weights rounded to 16 bits and packed as the B operand of the next product: slot
-        // (g, u) of chunk kb is row 32*kb + 16*(u/4) + 4*g + u%4.  lsum receives lacc plus the
-        // row sums 1^T W^T of the rounded weights (one MFMA against a tile of ones per chunk).
-        v4u wp[kQB][kNT / 32];
-        v4f lsum[kQB];
-        auto weights = [&](int qb, v4f lstart) __attribute__((always_inline)) {
-            lsum[qb] = lstart;
+        }
+        if constexpr (decltype(masked_tag)::value) {
 #pragma unroll
-            for (int kb = 0; kb < kNT / 32; ++kb) {
-                float w[8];
+            for (int t = 0; t < 4; ++t)
+                if (n0 + 16 * nb + 4 * g + t >= len) s[qb][nb][t] = -INFINITY;
+        }
+    };
+    // E(q): weights rounded to 16 bits and packed as the B operand of the next product: slot
+    // (g, u) of chunk kb is row 32*kb + 16*(u/4) + 4*g + u%4.  The row sums 1^T W^T of the
+    // rounded weights are added to lacc (one MFMA against a tile of ones per chunk); lold keeps
+    // the value from before the tile (all four registers of lacc are equal).
+    v4u wp[kQB][kNT / 32];
+    float lold[kQB];
+    auto weights = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) w[u] = __builtin_amdgcn_exp2f(s[qb][2 * kb + u / 4][u % 4]);
-                if constexpr (PREC == 0)
-                    wp[qb][kb] = v4u{pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]),
-                                     pack_bf16(w[6], w[7])};
-                else
-                    wp[qb][kb] = v4u{pack_f16_rtz(w[0], w[1]), pack_f16_rtz(w[2], w[3]),
-                                     pack_f16_rtz(w[4], w[5]), pack_f16_rtz(w[6], w[7])};
-                lsum[qb] = mma<PREC>(ones, wp[qb][kb], lsum[qb]);
+        for (int kb = 0; kb < kNT / 32; ++kb) {
+            float w[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) w[u] = __builtin_amdgcn_exp2f(s[qb][2 * kb + u / 4][u % 4]);
+            if constexpr (PREC == 0)
+                wp[qb][kb] = v4u{pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]),
+                                 pack_bf16(w[6], w[7])};
+            else
+                wp[qb][kb] = v4u{pack_f16_rtz(w[0], w[1]), pack_f16_rtz(w[2], w[3]),
+                                 pack_f16_rtz(w[4], w[5]), pack_f16_rtz(w[6], w[7])};
+            lacc[qb] = mma<PREC>(ones, wp[qb][kb], lacc[qb]);
+        }
+    };
+    // the weights of one 16-row block (four per lane), or of one half of it (two per lane)
+    auto weight_half = [&](int qb, int nb, int half) __attribute__((always_inline)) {
+        const float w0 = __builtin_amdgcn_exp2f(s[qb][nb][2 * half]);
+        const float w1 = __builtin_amdgcn_exp2f(s[qb][nb][2 * half + 1]);
+        wp[qb][nb / 2][2 * (nb & 1) + half] = PREC == 0 ? pack_bf16(w0, w1) : pack_f16_rtz(w0, w1);
+    };
+    auto weight_block = [&](int qb, int nb) __attribute__((always_inline)) {
+        weight_half(qb, nb, 0);
+        weight_half(qb, nb, 1);
+    };
+    // C(q): online softmax with a lazily updated reference: weights are exp2(s - mref) and may
+    // exceed one.  No maximum is taken on the common path: a weight above kBig shows in the
+    // tile's row sum, which the matrix unit delivers anyway, so the row sum is what is
+    // tested.  Only when it exceeds kBig (or is not finite), or on the first tile, is the
+    // tile maximum formed, mref moved there, Z and l rescaled and the weights recomputed.
+    // Every accepted weight is below kBig, far inside the range of the 16-bit formats, and
+    // kBig times the sequence length is far inside the float range.
+    auto settle = [&](int qb) __attribute__((always_inline)) {
+        const bool first = mref[qb] == -INFINITY;
+        const bool big = !(lacc[qb][0] - lold[qb] <= kBig);
+        if (__any(first || big)) {   // uniform over the wave, rare
+            float v = -INFINITY;
+#pragma unroll
+            for (int nb = 0; nb < kNT / 16; ++nb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) v = fmaxf(v, s[qb][nb][t]);
+            v = wave_xor_max(v, 16);
+            v = wave_xor_max(v, 32);   // tile maximum relative to mref; finite: a tile has a valid row
+            const float shift = (first || big) ? v : 0.f;
+            const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-shift);
+            mref[qb] = (first ? 0.f : mref[qb]) + shift;
+#pragma unroll
+            for (int nb = 0; nb < kNT / 16; ++nb) s[qb][nb] -= shift;
+            const float l0 = lold[qb] * alpha;
+            lacc[qb] = v4f{l0, l0, l0, l0};
+#pragma unroll
+            for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= alpha;
+            weights(qb);
+        }
+    };
+    // Z(q): Z^T += P^T W^T
+    auto accumulate = [&](int qb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kb = 0; kb < kNT / 32; ++kb) {
+#pragma unroll
+            for (int ib = 0; ib < RB; ++ib) {
+                z[qb][ib] = mma<PREC>(zah[kb][ib], wp[qb][kb], z[qb][ib]);
+                if constexpr (PREC == 0) z[qb][ib] = mma<PREC>(zal[kb][ib], wp[qb][kb], z[qb][ib]);
             }
-        };
-        // Online softmax with a lazily updated reference: weights are exp2(s - mref) and may
-        // exceed one.  No maximum is taken on the common path: a weight above kBig shows in the
-        // tile's row sum, which the matrix unit delivers anyway, so the row sum is what is
-        // tested.  Only when it exceeds kBig (or is not finite), or on the first tile, is the
-        // tile maximum formed, mref moved there, Z and l rescaled and the weights recomputed.
-        // Every accepted weight is below kBig, far inside the range of the 16-bit formats, and
-        // kBig times the sequence length is far inside the float range.
-        auto settle = [&](int qb) __attribute__((always_inline)) {
-            const bool first = mref[qb] == -INFINITY;
-            const bool big = !(lsum[qb][0] - lacc[qb][0] <= kBig);
-            if (__any(first || big)) {   // uniform over the wave, rare
-                float v = -INFINITY;
-#pragma unroll
-                for (int nb = 0; nb < kNT / 16; ++nb)
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) v = fmaxf(v, s[qb][nb][t]);
-                v = wave_xor_max(v, 16);
-                v = wave_xor_max(v, 32);   // tile maximum relative to mref; finite: a tile has a valid row
-                const float shift = (first || big) ? v : 0.f;
-                const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-shift);
-                mref[qb] = (first ? 0.f : mref[qb]) + shift;
-#pragma unroll
-                for (int nb = 0; nb < kNT / 16; ++nb) s[qb][nb] -= shift;
-                lacc[qb] *= alpha;
-#pragma unroll
-                for (int ib = 0; ib < RB; ++ib) z[qb][ib] *= alpha;
-                weights(qb, lacc[qb]);
-            }
-            lacc[qb] = lsum[qb];
-        };
-        // Z(q): Z^T += P^T W^T
-        v4u zah[kNT / 32][RB], zal[kNT / 32][RB];
-        auto load_zops = [&]() __attribute__((always_inline)) {
-#pragma unroll
-            for (int kb = 0; kb < kNT / 32; ++kb)
-#pragma unroll
-                for (int ib = 0; ib < RB; ++ib) {
-                    const int off = (16 * ib + i16) * LDT + 32 * kb + 4 * g;
-                    const uint2 h0 = *reinterpret_cast<const uint2*>(thi + off);
-                    const uint2 h1 = *reinterpret_cast<const uint2*>(thi + off + 16);
-                    zah[kb][ib] = v4u{h0.x, h0.y, h1.x, h1.y};
-                    if constexpr (PREC == 0) {
-                        const uint2 l0 = *reinterpret_cast<const uint2*>(tlo + off);
-                        const uint2 l1 = *reinterpret_cast<const uint2*>(tlo + off + 16);
-                        zal[kb][ib] = v4u{l0.x, l0.y, l1.x, l1.y};
-                    }
-                }
-        };
-        auto accumulate = [&](int qb) __attribute__((always_inline)) {
-#pragma unroll
-            for (int kb = 0; kb < kNT / 32; ++kb) {
-#pragma unroll
-                for (int ib = 0; ib < RB; ++ib) {
-                    z[qb][ib] = mma<PREC>(zah[kb][ib], wp[qb][kb], z[qb][ib]);
-                    if constexpr (PREC == 0) z[qb][ib] = mma<PREC>(zal[kb][ib], wp[qb][kb], z[qb][ib]);
-                }
-            }
-        };
-        constexpr int kSMfma = (kNT / 16) * RB2 * (PREC == 0 ? 3 : 1);   // MFMAs of one S(q)
-        constexpr int kZMfma = (kNT / 32) * (NIMG * RB);                 // MFMAs of one Z(q)
+        }
+    };
+    constexpr int kSMfma = (kNT / 16) * RB2 * (PREC == 0 ? 3 : 1);   // MFMAs of one S(q)
+    constexpr int kZMfma = (kNT / 32) * (NIMG * RB);                 // MFMAs of one Z(q)
+    constexpr int kLMfma = kNT / 32;                                 // MFMAs of the row sums of one E(q)
 
-        scores(0);
-        // S(1) on the matrix unit under exp(0) on the vector ALU
-        scores(1);
-        load_zops();
-        weights(0, lacc[0]);
+    // ---- the sequence loop, software-pipelined over tiles ---------------------------------
+    // Three tile buffers rotate: tile t is multiplied while tile t+1 already sits complete in
+    // the second buffer and tile t+2 is converted into the third.  That lets the scores of
+    // query block 0 of tile t+1 be issued inside tile t, so that every stage of the loop has
+    // work for the matrix unit and for the vector ALU side by side:
+    //   S(t,1) + E(t,0) | C(t,0) | Z(t,0) + S(t+1,0) + E(t,1) | C(t,1) | Z(t,1) + convert(t+2)
+    // NEXT: 0 = no following tile, 1 = a full one, 2 = the ragged last one.
+    const int ntiles = ceil_div(len, kNT);
+    const int nfull = len / kNT;
+    auto do_tile = [&](int tile, auto cur_masked, auto next_tag) __attribute__((always_inline)) {
+        constexpr int NEXT = decltype(next_tag)::value;
+        const uint16_t* bufc = tiles + (tile % 3) * kBuf;
+        const uint16_t* bufn = tiles + ((tile + 1) % 3) * kBuf;
+        uint16_t* bufw = tiles + ((tile + 2) % 3) * kBuf;
+        const bool ahead = tile + 2 < ntiles;
+        if (ahead) fetch(tile + 2);
+
+        // The order of issue is written out by hand and fenced, because the instruction
+        // scheduler otherwise bunches the matrix and the vector work of a stage.  A stage is
+        // kNB slots; a slot issues its share of the stage's matrix units, the four
+        // exponentials of one 16-row block and the two packs of the block before (a pack right
+        // behind its exponentials would wait for them; issued a slot later it falls into the
+        // shadow of the transcendental unit).
+        constexpr int kNB = kNT / 16;
+        constexpr int kUZ = (kNT / 32) * RB;   // Z units of a query block
+        auto z_unit = [&](int qb, int u) __attribute__((always_inline)) {
+            const int kb = u / RB, ib = u % RB;
+            z[qb][ib] = mma<PREC>(zah[kb][ib], wp[qb][kb], z[qb][ib]);
+            if constexpr (PREC == 0) z[qb][ib] = mma<PREC>(zal[kb][ib], wp[qb][kb], z[qb][ib]);
+        };
+        auto stage_of = [&](int qe, auto nunits_tag, auto&& unit) __attribute__((always_inline)) {
+            constexpr int nunits = decltype(nunits_tag)::value;
+            float wprev[4], wcur[4];
+            lold[qe] = lacc[qe][0];
 #pragma unroll
-        for (int i = 0; i < kSMfma; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // two VALU
-        }
+            for (int nb = 0; nb < kNB; ++nb) {
+                // the row sums of a chunk whose second pack was issued one slot ago
+                if (nb >= 3 && (nb & 1) == 1) lacc[qe] = mma<PREC>(ones, wp[qe][(nb - 3) / 2], lacc[qe]);
+#pragma unroll
+                for (int u = nb * nunits / kNB; u < (nb + 1) * nunits / kNB; ++u) unit(u);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) wcur[t] = __builtin_amdgcn_exp2f(s[qe][nb][t]);
+                if (nb > 0) {
+                    wp[qe][(nb - 1) / 2][2 * ((nb - 1) & 1)] = pack_w<PREC>(wprev[0], wprev[1]);
+                    wp[qe][(nb - 1) / 2][2 * ((nb - 1) & 1) + 1] = pack_w<PREC>(wprev[2], wprev[3]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) wprev[t] = wcur[t];
+            }
+            wp[qe][(kNB - 1) / 2][2 * ((kNB - 1) & 1)] = pack_w<PREC>(wprev[0], wprev[1]);
+            wp[qe][(kNB - 1) / 2][2 * ((kNB - 1) & 1) + 1] = pack_w<PREC>(wprev[2], wprev[3]);
+            lacc[qe] = mma<PREC>(ones, wp[qe][kNB / 2 - 1], lacc[qe]);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // stage 1: E(t,0) next to Z(t-1,1), then S(t,1); the Z operands of this tile are read
+        // once the last product with the previous tile's operands is issued
+        stage_of(0, std::integral_constant<int, kUZ + kNB>{}, [&](int u) __attribute__((always_inline)) {
+            if (u < kUZ) {
+                z_unit(1, u);
+            } else {
+                if (u == kUZ) load_zops(bufc);
+                score_block(1, u - kUZ, tile * kNT, cur_masked);
+            }
+        });
+        if (ahead) commit(bufw);
         settle(0);
-        // Z(0) under exp(1)
-        accumulate(0);
-        weights(1, lacc[1]);
-#pragma unroll
-        for (int i = 0; i < kZMfma; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-        }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (NEXT != 0) load_sops(bufn);
+        // stage 2: E(t,1) next to Z(t,0), then S(t+1,0)
+        stage_of(1, std::integral_constant<int, kUZ + (NEXT != 0 ? kNB : 0)>{}, [&](int u) __attribute__((always_inline)) {
+            if (u < kUZ) z_unit(0, u);
+            else score_block(0, u - kUZ, (tile + 1) * kNT, std::integral_constant<bool, NEXT == 2>{});
+        });
         settle(1);
-        // Z(1) under the split of the next tile
-        accumulate(1);
-        if (more) commit(tiles + ((tile + 1) & 1) * kBuf);
         __syncthreads();
     };
-    const int nfull = len / kNT;
-    for (int tile = 0; tile < nfull; ++tile) do_tile(tile, std::false_type{});
-    if (nfull < ntiles) do_tile(nfull, std::true_type{});
+    // Z(t,1) trails its tile by one stage; before the first tile its operands are zero
+#pragma unroll
+    for (int kb = 0; kb < kNT / 32; ++kb) {
+        wp[1][kb] = v4u{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int ib = 0; ib < RB; ++ib) {
+            zah[kb][ib] = v4u{0u, 0u, 0u, 0u};
+            zal[kb][ib] = v4u{0u, 0u, 0u, 0u};
+        }
+    }
+    if (ntiles > 0) { fetch(0); commit(tiles); }
+    if (ntiles > 1) { fetch(1); commit(tiles + kBuf); }
+    __syncthreads();
+    if (ntiles > 0) {
+        load_sops(tiles);
+        if (nfull == 0) scores(0, 0, std::true_type{});
+        else scores(0, 0, std::false_type{});
+    }
+    using tag0 = std::integral_constant<int, 0>;
+    using tag1 = std::integral_constant<int, 1>;
+    using tag2 = std::integral_constant<int, 2>;
+    // full tiles followed by a full tile
+    for (int tile = 0; tile + 1 < nfull; ++tile) do_tile(tile, std::false_type{}, tag1{});
+    if (nfull > 0) {
+        if (nfull < ntiles) do_tile(nfull - 1, std::false_type{}, tag2{});
+        else do_tile(nfull - 1, std::false_type{}, tag0{});
+    }
+    if (nfull < ntiles) do_tile(nfull, std::true_type{}, tag0{});
+    if (ntiles > 0) accumulate(1);
 
     // ---- epilogue in float: O^T = V (Z / l)^T ------------------------------------------
 #pragma unroll
@@ -460,8 +571,9 @@ hipError_t launch_t(const void* Q, const float* S, const float* V, const float* 
                     hipStream_t stream) {
     constexpr int RP = 32 * RB2;
     constexpr int NIMG = PREC == 0 ? 2 : 1;
+    constexpr int kNT = tile_rows<PREC, RB2>();
     const size_t lds = sizeof(float) * (size_t)D * (RP + 4) +
-                       sizeof(uint16_t) * 2 * NIMG *
+                       sizeof(uint16_t) * 3 * NIMG *
                            ((size_t)kNT * (RP + SOLAR_ATTN_RPAD) + (size_t)RP * (kNT + 12));
     dim3 grid(ceil_div(M, kWaves * kQB * 16) * 8 * ceil_div(B, 8)), block(kThreads);
     auto kern = attention_seq_bf16_kernel<D, RB2, true, PREC>;
