@@ -87,6 +87,14 @@ __device__ __forceinline__ uint32_t pack_f16_rtz(float a, float b) {
     return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
 }
 
+// transposing 64-bit LDS read of 16-bit elements (see load_zops for the lane mapping)
+__device__ __forceinline__ uint2 lds_read_tr16(const uint16_t* p) {
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
+    const v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(p));
+    return __builtin_bit_cast(uint2, v);
+}
+
 template <int PREC>
 __device__ __forceinline__ uint32_t pack_w(float a, float b);
 
@@ -116,10 +124,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
 #define SOLAR_ATTN_RPAD 4
 #endif
     constexpr int LDR = RP + SOLAR_ATTN_RPAD;   // bf16 elements, row-major image  [kNT][LDR]
-    constexpr int LDT = kNT + 12;         // bf16 elements, transposed image [RP][LDT]
-    constexpr int kImg = kNT * LDR;       // elements of one row-major image
-    constexpr int kImgT = RP * LDT;       // elements of one transposed image
-    constexpr int kBuf = NIMG * (kImg + kImgT);  // row-major head (, tail); transposed head (, tail)
+    constexpr int kImg = kNT * LDR;       // elements of one image
+    constexpr int kBuf = NIMG * kImg;     // head (, tail)
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                                             // [D][LDV]
     uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);  // [3][kBuf]
@@ -135,10 +141,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     const int m_wave = (slot % mtiles) * (kWaves * kQB * 16) + wave * (kQB * 16);
     const float* Pb = P + (size_t)b * N * r;
     // PREC 1: P is scaled into [-1, 1] by the largest singular value before it is rounded
+    // when it lies outside [1, 2^13]; inside that range fp16 holds P as it is
     float pscale = 1.f, punscale = 1.f;
+    bool rescale = false;
     if constexpr (PREC == 1) {
         const float s0 = S[(size_t)b * r];
-        if (s0 > 0.f) { pscale = 1.f / s0; punscale = s0; }
+        rescale = s0 > 0.f && !(s0 >= 1.f && s0 <= 8192.f);
+        if (rescale) { pscale = 1.f / s0; punscale = s0; }
     }
 
     for (int e = tid; e < D * RP; e += kThreads) {
@@ -209,65 +218,54 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
     const uint32_t one2 = PREC == 0 ? 0x3f803f80u : 0x3c003c00u;   // two ones (bf16 / fp16)
     const v4u ones = v4u{one2, one2, one2, one2};
 
-    // ---- tile loader: float P -> (hi, lo) bf16, row-major and transposed ---------------
-    // A thread owns two consecutive rows and four consecutive ranks, so that the transposed
-    // image is written as 32-bit words (two rows of one rank).
-    const int quads_per_row = r >> 2;                      // r % 4 == 0 on this path
-    constexpr int kMaxLoads = ((kNT / 2) * (RP / 4) + kThreads - 1) / kThreads;
+    // ---- tile loader: float P -> 16-bit image(s) [kNT][LDR] ------------------------------
+    // A thread owns two consecutive rows and four consecutive ranks of a tile.  The loads carry
+    // no predicate (rows and ranks are clamped into the user's P instead), so that nothing but
+    // the loads themselves sits between their issue and the conversion a stage later; rows past
+    // the valid length are zeroed when a ragged tile is converted.
+    constexpr int kQuads = RP / 4;
+    constexpr int kTasks = (kNT / 2) * kQuads;
+    constexpr int kMaxLoads = (kTasks + kThreads - 1) / kThreads;
     v4f stage[kMaxLoads][2];
     auto fetch = [&](int tile) __attribute__((always_inline)) {
         const int n0 = tile * kNT;
 #pragma unroll
         for (int i = 0; i < kMaxLoads; ++i) {
             const int e = tid + i * kThreads;
-            const int np = e / quads_per_row, c4 = e % quads_per_row;
+            const int np = e / kQuads, c4 = min(e % kQuads, (r >> 2) - 1);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int n = n0 + 2 * np + h;
-                stage[i][h] = v4f{0.f, 0.f, 0.f, 0.f};
-                if (np < kNT / 2 && n < len)
-                    stage[i][h] = *reinterpret_cast<const v4f*>(Pb + (size_t)n * r + 4 * c4);
+                const int n = min(n0 + 2 * np + h, len - 1);
+                stage[i][h] = *reinterpret_cast<const v4f*>(Pb + (size_t)n * r + 4 * c4);
             }
         }
     };
-    auto commit = [&](uint16_t* buf) __attribute__((always_inline)) {
+    auto commit = [&](uint16_t* buf, int tile, auto masked_tag) __attribute__((always_inline)) {
         uint16_t* rhi = buf;
-        uint16_t* rlo = buf + (NIMG - 1) * kImg;
-        uint16_t* thi = buf + NIMG * kImg;
-        uint16_t* tlo = thi + (NIMG - 1) * kImgT;
+        const int n0 = tile * kNT;
 #pragma unroll
         for (int i = 0; i < kMaxLoads; ++i) {
             const int e = tid + i * kThreads;
-            const int np = e / quads_per_row, c4 = e % quads_per_row;
-            if (np < kNT / 2) {
-                if constexpr (PREC == 0) {
-                    float h[2][4], l[2][4];
+            const int np = e / kQuads, c4 = e % kQuads;
+            if ((kTasks % kThreads == 0 || e < kTasks) && 4 * c4 < r) {
 #pragma unroll
-                    for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) split_bf16(stage[i][hh][c], h[hh][c], l[hh][c]);
-#pragma unroll
-                    for (int hh = 0; hh < 2; ++hh) {
-                        const int nn = 2 * np + hh;
-                        *reinterpret_cast<uint2*>(rhi + nn * LDR + 4 * c4) =
-                            uint2{pack_bf16(h[hh][0], h[hh][1]), pack_bf16(h[hh][2], h[hh][3])};
-                        *reinterpret_cast<uint2*>(rlo + nn * LDR + 4 * c4) =
-                            uint2{pack_bf16(l[hh][0], l[hh][1]), pack_bf16(l[hh][2], l[hh][3])};
+                for (int hh = 0; hh < 2; ++hh) {
+                    uint16_t* dst = rhi + (2 * np + hh) * LDR + 4 * c4;
+                    v4f x = stage[i][hh];
+                    if constexpr (decltype(masked_tag)::value) {
+                        if (n0 + 2 * np + hh >= len) x = v4f{0.f, 0.f, 0.f, 0.f};
                     }
+                    if constexpr (PREC == 0) {
+                        float h[4], l[4];
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        *reinterpret_cast<uint32_t*>(thi + (4 * c4 + c) * LDT + 2 * np) = pack_bf16(h[0][c], h[1][c]);
-                        *reinterpret_cast<uint32_t*>(tlo + (4 * c4 + c) * LDT + 2 * np) = pack_bf16(l[0][c], l[1][c]);
+                        for (int c = 0; c < 4; ++c) split_bf16(x[c], h[c], l[c]);
+                        *reinterpret_cast<uint2*>(dst) = uint2{pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3])};
+                        *reinterpret_cast<uint2*>(dst + (NIMG - 1) * kImg) =
+                            uint2{pack_bf16(l[0], l[1]), pack_bf16(l[2], l[3])};
+                    } else {
+                        if (rescale) x *= pscale;   // uniform over the workgroup
+                        *reinterpret_cast<uint2*>(dst) = uint2{pack_f16(x[0], x[1]), pack_f16(x[2], x[3])};
                     }
-                } else {
-                    const v4f x0 = stage[i][0] * pscale, x1 = stage[i][1] * pscale;
-                    *reinterpret_cast<uint2*>(rhi + (2 * np) * LDR + 4 * c4) =
-                        uint2{pack_f16(x0[0], x0[1]), pack_f16(x0[2], x0[3])};
-                    *reinterpret_cast<uint2*>(rhi + (2 * np + 1) * LDR + 4 * c4) =
-                        uint2{pack_f16(x1[0], x1[1]), pack_f16(x1[2], x1[3])};
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        *reinterpret_cast<uint32_t*>(thi + (4 * c4 + c) * LDT + 2 * np) = pack_f16(x0[c], x1[c]);
                 }
             }
         }
@@ -295,23 +293,27 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
                 }
             }
     };
-    // A operands of Z^T += P^T W^T: 16 ranks per block, 32 rows of the tile per chunk
-    // (transposed image).
+    // A operands of Z^T += P^T W^T: 16 ranks per block, 32 rows of the tile per chunk, slot
+    // (g, u) = row 32*kb + 16*(u/4) + 4*g + u%4.  They come out of the same row-major image
+    // through the transposing LDS read: within a group of 16 lanes, lane i passes the address
+    // of four consecutive 16-bit elements and receives element i%4 of the lanes i/4, 4 + i/4,
+    // 8 + i/4, 12 + i/4.  So lane i points at row 4*g + i/4, ranks 16*ib + 4*(i%4) ..+3, and
+    // gets rank 16*ib + i of rows 4*g .. 4*g+3.
     v4u zah[kNT / 32][RB], zal[kNT / 32][RB];
     auto load_zops = [&](const uint16_t* buf) __attribute__((always_inline)) {
-        const uint16_t* thi = buf + NIMG * kImg;
-        const uint16_t* tlo = thi + (NIMG - 1) * kImgT;
+        const uint16_t* rhi = buf;
+        const uint16_t* rlo = buf + (NIMG - 1) * kImg;
 #pragma unroll
         for (int kb = 0; kb < kNT / 32; ++kb)
 #pragma unroll
             for (int ib = 0; ib < RB; ++ib) {
-                const int off = (16 * ib + i16) * LDT + 32 * kb + 4 * g;
-                const uint2 h0 = *reinterpret_cast<const uint2*>(thi + off);
-                const uint2 h1 = *reinterpret_cast<const uint2*>(thi + off + 16);
+                const int off = (32 * kb + 4 * g + (i16 >> 2)) * LDR + 16 * ib + 4 * (i16 & 3);
+                const uint2 h0 = lds_read_tr16(rhi + off);
+                const uint2 h1 = lds_read_tr16(rhi + off + 16 * LDR);
                 zah[kb][ib] = v4u{h0.x, h0.y, h1.x, h1.y};
                 if constexpr (PREC == 0) {
-                    const uint2 l0 = *reinterpret_cast<const uint2*>(tlo + off);
-                    const uint2 l1 = *reinterpret_cast<const uint2*>(tlo + off + 16);
+                    const uint2 l0 = lds_read_tr16(rlo + off);
+                    const uint2 l1 = lds_read_tr16(rlo + off + 16 * LDR);
                     zal[kb][ib] = v4u{l0.x, l0.y, l1.x, l1.y};
                 }
             }
@@ -492,17 +494,15 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
             lacc[qe] = mma<PREC>(ones, wp[qe][kNB / 2 - 1], lacc[qe]);
             __builtin_amdgcn_sched_barrier(0);
         };
-        // stage 1: E(t,0) next to Z(t-1,1), then S(t,1); the Z operands of this tile are read
+        // stage 1: E(t,0) next to S(t,1), then Z(t-1,1); the Z operands of this tile are read
         // once the last product with the previous tile's operands is issued
         stage_of(0, std::integral_constant<int, kUZ + kNB>{}, [&](int u) __attribute__((always_inline)) {
-            if (u < kUZ) {
-                z_unit(1, u);
-            } else {
-                if (u == kUZ) load_zops(bufc);
-                score_block(1, u - kUZ, tile * kNT, cur_masked);
-            }
+            if (u < kNB) score_block(1, u, tile * kNT, cur_masked);
+            else z_unit(1, u - kNB);
         });
-        if (ahead) commit(bufw);
+        load_zops(bufc);
+        if (tile + 2 < nfull) commit(bufw, tile + 2, std::false_type{});
+        else if (ahead) commit(bufw, tile + 2, std::true_type{});
         settle(0);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (NEXT != 0) load_sops(bufn);
@@ -524,8 +524,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
             zal[kb][ib] = v4u{0u, 0u, 0u, 0u};
         }
     }
-    if (ntiles > 0) { fetch(0); commit(tiles); }
-    if (ntiles > 1) { fetch(1); commit(tiles + kBuf); }
+    if (ntiles > 0) { fetch(0); commit(tiles, 0, std::true_type{}); }
+    if (ntiles > 1) { fetch(1); commit(tiles + kBuf, 1, std::true_type{}); }
     __syncthreads();
     if (ntiles > 0) {
         load_sops(tiles);
@@ -573,8 +573,7 @@ hipError_t launch_t(const void* Q, const float* S, const float* V, const float* 
     constexpr int NIMG = PREC == 0 ? 2 : 1;
     constexpr int kNT = tile_rows<PREC, RB2>();
     const size_t lds = sizeof(float) * (size_t)D * (RP + 4) +
-                       sizeof(uint16_t) * 3 * NIMG *
-                           ((size_t)kNT * (RP + SOLAR_ATTN_RPAD) + (size_t)RP * (kNT + 12));
+                       sizeof(uint16_t) * 3 * NIMG * ((size_t)kNT * (RP + SOLAR_ATTN_RPAD));
     dim3 grid(ceil_div(M, kWaves * kQB * 16) * 8 * ceil_div(B, 8)), block(kThreads);
     auto kern = attention_seq_bf16_kernel<D, RB2, true, PREC>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
