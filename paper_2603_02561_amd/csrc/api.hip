@@ -167,7 +167,10 @@ solar_status solar_svd_attention(const void* Q, const float* S, const float* V, 
             // (2e-2 contract), bf16 head + tail operands (about 16 mantissa bits in the scores)
             // when SOLAR_ATTN_SPLIT is set or S is not supplied; float inputs keep float
             // arithmetic throughout
-            if (bf16 && attention_seq_bf16_supported(d, r) && !std::getenv("SOLAR_ATTN_F32"))
+            if (bf16 && S && attention_seq_x32_supported(d, r) && !std::getenv("SOLAR_ATTN_F32") &&
+                !std::getenv("SOLAR_ATTN_SPLIT") && !std::getenv("SOLAR_ATTN_X16"))
+                e = launch_attention_seq_x32(Q, S, V, P, lengths, B, N, d, r, M, scale, O, st);
+            else if (bf16 && attention_seq_bf16_supported(d, r) && !std::getenv("SOLAR_ATTN_F32"))
                 e = launch_attention_seq_bf16(Q, S, V, P, lengths, B, N, d, r, M, scale,
                                               std::getenv("SOLAR_ATTN_SPLIT") != nullptr, O, st);
             else

@@ -1,0 +1,456 @@
+// SVD-Attention in its sequence-softmax form, O = softmax_n(scale * Qt P^T) P V^T
+// (Section "SVD-Attention"; Qt = Q V, P = X V), fast path for bf16 inputs and rank <= 32
+// on the 32x32x16 fp16 matrix instruction of gfx950.
+//
+// The kernel is bound by the issue port of the vector ALU, which the matrix instructions
+// share: every MFMA holds the port for about eight cycles whatever its shape, an
+// exponential for about eight (half rate), and the ordinary instructions that follow an
+// exponential (packs, dot products) fall into the second half of its slot for free.  Hence
+//   * 32x32x16 products: one instruction covers 1024 scores where the 16x16x32 shape covers
+//     256, so a block of 32 rows of P against 32 queries costs two MFMAs for the scores and
+//     two for Z^T += P^T W^T;
+//   * row sums of the rounded weights by one more MFMA per 16 rows against a tile of ones:
+//     it costs the issue port a fraction of what a chain of dependent vector adds or packed
+//     dot products costs (their result latency is exposed), and the matrix pipe has room;
+//   * the softmax reference moves lazily: a block's scores are only compared against it
+//     (a maximum over the lane's 16 scores, taken while the block before is exponentiated).
+//
+// P and Qt are rounded to fp16 once (11-bit significands; P is first scaled by 1/S[0] when
+// S[0] lies outside [1, 2^13]); the scores carry about 2^-11 relative error, inside the 2e-2
+// contract for bf16 inputs.  Accumulation is in float throughout.
+//
+// As in the other attention kernels the products are evaluated transposed (S^T = P Qt^T,
+// Z^T = P^T W^T) so that a query is a lane (lane l and l+32 share query l%32 and split the
+// rows of a block): the accumulators of the score product are the B operand of the Z
+// product without any data movement, because the contraction index can be enumerated in any
+// order as long as both operands agree.  Register t of a 32x32 accumulator in lane l is row
+// 8*(t/4) + 4*(l/32) + t%4, so contraction slot u (0..7) of lane half h is
+//   * rank 16*c + 8*(u/4) + 4*h + u%4 for chunk c of the score product: the loader stores
+//     rank quads 1 and 2 of every 16 ranks swapped, which makes a lane's eight ranks one
+//     16-byte LDS read;
+//   * row 16*c + 8*(u/4) + 4*h + u%4 of the block for chunk c of the Z product: two
+//     transposing LDS reads (four rows each) out of the same row-major image.
+//
+// A workgroup is eight waves of 32 queries.  The sequence is walked in tiles of 128 rows
+// through three LDS buffers (one being multiplied, the next complete, the third being
+// converted) and, inside a tile, in blocks of 32 rows through a software pipeline: while the
+// exponentials of block j run, the matrix unit computes the scores of block j+1 and adds
+// block j-1 to Z.
+#include <type_traits>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace solar {
+
+namespace {
+
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kQW = 32;              // queries per wave
+constexpr int kNT = 128;             // rows of P per tile
+constexpr int kNB = kNT / 32;        // blocks per tile
+constexpr int RP = 32;               // padded rank
+constexpr int LDV = RP + 1;          // floats, V image [D][LDV]
+constexpr int LDR = RP + 8;          // fp16 elements, tile image [kNT][LDR]
+constexpr int kBuf = kNT * LDR;      // elements of one tile buffer
+constexpr float kLog2e = 1.4426950408889634f;
+// a score more than kShift (in log2 units) above the reference moves the reference there, so
+// no weight exceeds 2^kShift: far inside the fp16 range, and the row sums stay far inside float
+#ifndef SOLAR_X32_KSHIFT
+#define SOLAR_X32_KSHIFT 8.f
+#endif
+constexpr float kShift = SOLAR_X32_KSHIFT;
+
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ v16f mma32(v4u a, v4u b, v16f c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c,
+                                                  0, 0, 0);
+}
+
+// two floats -> packed fp16, round to nearest even (operands that are prepared once)
+__device__ __forceinline__ uint32_t pack_f16(float a, float b) {
+    v2h v = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// two floats -> packed fp16 in one instruction, round toward zero (softmax weights; their
+// row sum is taken from the rounded values, so the rounding direction cancels)
+__device__ __forceinline__ uint32_t pack_f16_rtz(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+
+// transposing 64-bit LDS read of 16-bit elements: within a group of 16 lanes, lane i passes
+// the address of four consecutive elements and receives element i%4 of the lanes i/4,
+// 4 + i/4, 8 + i/4, 12 + i/4
+__device__ __forceinline__ uint2 lds_read_tr16(const uint16_t* p) {
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
+    const v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(p));
+    return __builtin_bit_cast(uint2, v);
+}
+
+// position of rank quad c4 (ranks 4*c4 .. 4*c4+3) in a row of the tile image: quads 1 and 2
+// of every 16 ranks are swapped
+__device__ __forceinline__ int quad_pos(int c4) { return (c4 & ~3) | ((c4 & 1) << 1) | ((c4 >> 1) & 1); }
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
+    const void* __restrict__ Qv, const float* __restrict__ S, const float* __restrict__ V,
+    const float* __restrict__ P, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
+    float scale, float* __restrict__ O) {
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float* Vs = smem;                                              // [D][LDV]
+    uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);   // [3][kBuf]
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id.  All M-tiles of a user
+    // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
+    const int mtiles = ceil_div(M, kWaves * kQW);
+    const int slot_id = blockIdx.x >> 3;
+    const int b = (slot_id / mtiles) * 8 + (blockIdx.x & 7);
+    if (b >= B) return;   // uniform over the workgroup
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n32 = lane & 31, h = lane >> 5;
+    const int len = user_len(lengths, b, N);
+    const int m_wave = (slot_id % mtiles) * (kWaves * kQW) + wave * kQW;
+    const float* Pb = P + (size_t)b * N * r;
+    // P is scaled into [-1, 1] by the largest singular value before it is rounded to fp16
+    // when that value lies outside [1, 2^13]; inside that range fp16 holds P as it is
+    float pscale = 1.f, punscale = 1.f;
+    bool rescale = false;
+    {
+        const float s0 = S[(size_t)b * r];
+        rescale = s0 > 0.f && !(s0 >= 1.f && s0 <= 8192.f);
+        if (rescale) { pscale = 1.f / s0; punscale = s0; }
+    }
+
+    for (int e = tid; e < D * RP; e += kThreads) {
+        const int k = e / RP, c = e % RP;
+        Vs[k * LDV + c] = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
+    }
+    // zero the tile buffers once: padded rank columns stay zero for ever
+    for (int e = tid; e < 3 * kBuf / 2; e += kThreads) reinterpret_cast<uint32_t*>(tiles)[e] = 0u;
+    __syncthreads();
+
+    // ---- prologue: Qt^T = V^T Q^T in float (32x32x2 MFMA; the contraction slot of lane half
+    // h in step s is coordinate (D/2)*h + s), scaled by scale*log2(e), rounded to fp16 -------
+    v4u qB[2];
+    {
+        v16f qt;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) qt[t] = 0.f;
+        const int m = m_wave + n32;
+        const bool valid = m < M;
+        const uint16_t* qrow = reinterpret_cast<const uint16_t*>(Qv) + ((size_t)b * M + (valid ? m : 0)) * D +
+                               (D / 2) * h;
+        const float* vcol = Vs + (D / 2) * h * LDV + n32;
+        for (int cc = 0; cc < D / 16; ++cc) {
+            v4u w = *reinterpret_cast<const v4u*>(qrow + 8 * cc);
+            if (!valid) w = v4u{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                qt = __builtin_amdgcn_mfma_f32_32x32x2f32(vcol[(8 * cc + 2 * e) * LDV], bf16_lo(w[e]), qt, 0, 0, 0);
+                qt = __builtin_amdgcn_mfma_f32_32x32x2f32(vcol[(8 * cc + 2 * e + 1) * LDV], bf16_hi(w[e]), qt, 0, 0, 0);
+            }
+        }
+        // B operand of the score product, chunk c: slot u of lane half h is register 8*c + u
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            float q[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                q[u] = fminf(fmaxf(qt[8 * c + u] * (scale * kLog2e * punscale), -6.0e4f), 6.0e4f);
+            qB[c] = v4u{pack_f16(q[0], q[1]), pack_f16(q[2], q[3]), pack_f16(q[4], q[5]), pack_f16(q[6], q[7])};
+        }
+    }
+
+    // ---- tile loader: float P -> fp16 image [kNT][LDR] ------------------------------------
+    // A thread owns two consecutive rows and four consecutive ranks of a tile.  The loads carry
+    // no predicate: byte offsets into the user's P advance by one tile per fetch, and for a
+    // ragged last tile the rows are clamped to the last valid one (they are zeroed when that
+    // tile is converted).  Rank quads at or beyond r load quad r/4-1 and are never stored.
+    constexpr int kQuads = RP / 4;
+    static_assert((kNT / 2) * kQuads == kThreads, "one loader task per thread");
+    const int ld_np = tid / kQuads, ld_c4 = tid % kQuads;
+    const bool ld_active = 4 * ld_c4 < r;
+    const int ld_dst = (2 * ld_np) * LDR + 4 * quad_pos(ld_c4);
+    const uint32_t row_bytes = 4u * (uint32_t)r;
+    const uint32_t ld_col = 16u * (uint32_t)min(ld_c4, (r >> 2) - 1);
+    const int nfull = len / kNT;   // tiles whose rows are all valid
+    const char* Pbytes = reinterpret_cast<const char*>(Pb);
+    uint32_t ld_off = (uint32_t)(2 * ld_np) * row_bytes + ld_col;   // row 2*ld_np of the next tile to fetch
+    v4f stage[2];
+    auto fetch = [&](int tile) __attribute__((always_inline)) {
+        uint32_t o0 = ld_off, o1 = ld_off + row_bytes;
+        if (__builtin_expect(tile >= nfull, 0)) {   // uniform: the ragged last tile
+            const int n0 = min(tile * kNT + 2 * ld_np, len - 1), n1 = min(tile * kNT + 2 * ld_np + 1, len - 1);
+            o0 = (uint32_t)n0 * row_bytes + ld_col;
+            o1 = (uint32_t)n1 * row_bytes + ld_col;
+        }
+        stage[0] = *reinterpret_cast<const v4f*>(Pbytes + o0);
+        stage[1] = *reinterpret_cast<const v4f*>(Pbytes + o1);
+        ld_off += (uint32_t)kNT * row_bytes;
+    };
+    auto commit = [&](uint16_t* buf, int tile) __attribute__((always_inline)) {
+        if (ld_active) {
+            v4f x0 = stage[0], x1 = stage[1];
+            if (__builtin_expect(tile >= nfull, 0)) {   // uniform
+                if (tile * kNT + 2 * ld_np >= len) x0 = v4f{0.f, 0.f, 0.f, 0.f};
+                if (tile * kNT + 2 * ld_np + 1 >= len) x1 = v4f{0.f, 0.f, 0.f, 0.f};
+            }
+            if (__builtin_expect(rescale, 0)) { x0 *= pscale; x1 *= pscale; }   // uniform
+            uint16_t* dst = buf + ld_dst;
+            *reinterpret_cast<uint2*>(dst) = uint2{pack_f16(x0[0], x0[1]), pack_f16(x0[2], x0[3])};
+            *reinterpret_cast<uint2*>(dst + LDR) = uint2{pack_f16(x1[0], x1[1]), pack_f16(x1[2], x1[3])};
+        }
+    };
+
+    // ---- operands of a block ----------------------------------------------------------------
+    // score product: lane (row n32 of the block, half h) reads image positions 16*c + 8*h ..+7
+    const int sa_off = n32 * LDR + 8 * h;
+    // Z product: lanes 16*G .. 16*G+15 receive ranks 16*(G%2) .. +15 for the rows of lane half
+    // G/2; lane i of the group points at row 4*(G/2) + i/4 (+8 for the second read, +16 for
+    // the second chunk), rank quad 4*(G%2) + i%4
+    const int za_off = (4 * h + ((lane & 15) >> 2)) * LDR + 4 * quad_pos(4 * ((lane >> 4) & 1) + (lane & 3));
+    v4u sA[2][2], zA[2][2];     // [block parity][chunk]
+
+    // ---- state --------------------------------------------------------------------------------
+    v16f s[2];          // scores of two consecutive blocks, relative to mref
+    v4u wp[2][2];       // packed weights [block parity][chunk]
+    v16f z;             // Z^T, rank 8*(t/4) + 4*h + t%4 of query n32
+    v16f cinit;         // -mref in every register: start value of the score accumulators
+    v16f lacc;          // row sum of the weights of query n32 in every register
+    float mref = 0.f;
+    float smax = 0.f;   // largest score of the lane in the block that is exponentiated next
+    const v4u ones = v4u{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};   // eight fp16 ones
+#pragma unroll
+    for (int t = 0; t < 16; ++t) { z[t] = 0.f; cinit[t] = 0.f; lacc[t] = 0.f; }
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        wp[0][c] = wp[1][c] = v4u{0u, 0u, 0u, 0u};
+        zA[0][c] = zA[1][c] = v4u{0u, 0u, 0u, 0u};
+    }
+
+    // Online softmax with a lazily updated reference: weights are exp2(s - mref) and may exceed
+    // one.  The scores of a block are compared with the reference before they are
+    // exponentiated; only when one of them exceeds it by more than kShift (or for the first
+    // block) is the block maximum formed per query, mref moved there for the queries that need
+    // it, and everything that is relative to the old reference rescaled: Z, the row sums and
+    // the packed weights of the block before, whose Z product is still to be issued.
+    auto move_reference = [&](int cur, bool first) __attribute__((always_inline)) {
+        float v = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) v = fmaxf(v, s[cur][t]);
+        v = wave_xor_max(v, 32);   // block maximum of the query, relative to mref
+        const float shift = (first || v > kShift) ? v : 0.f;
+        const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-shift);
+        mref += shift;
+        const _Float16 ah = (_Float16)alpha;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            s[cur][t] -= shift;
+            z[t] *= alpha;
+            lacc[t] *= alpha;
+            cinit[t] = -mref;
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            wp[cur ^ 1][c] = __builtin_bit_cast(v4u, __builtin_bit_cast(v8h, wp[cur ^ 1][c]) * ah);
+    };
+    // rows of the block past the valid length get weight zero
+    auto mask_block = [&](int cur, int j) __attribute__((always_inline)) {
+        if (__builtin_expect((j + 1) * 32 > len, 0)) {   // uniform, only the last block
+#pragma unroll
+            for (int t = 0; t < 16; ++t)
+                if (j * 32 + 8 * (t / 4) + 4 * h + (t % 4) >= len) s[cur][t] = -INFINITY;
+        }
+    };
+
+    // One slot of the pipeline, block j of parity cur = j % 2: E(j) on the vector ALU next to
+    // S(j+1), Z(j-1) and the row sums of block j on the matrix unit, the maximum of the scores
+    // of block j+1, and the LDS reads for S(j+2) and Z(j).  The order
+    // of issue is written out and fenced pair by pair: an exponential occupies the
+    // transcendental unit for two issue slots, and the instruction placed right behind it
+    // (a pack or a row sum of the group of exponentials before, an LDS read) issues in its
+    // shadow; bunched behind four exponentials those instructions would each cost a slot.
+    // sa_next and za_this point at the score operands of block j+2 and the Z operands of block j.
+#define SOLAR_FENCE __builtin_amdgcn_sched_barrier(0)
+    auto slot = [&](int j, auto cur_tag, const uint16_t* sa_next, const uint16_t* za_this)
+                    __attribute__((always_inline)) {
+        constexpr int cur = decltype(cur_tag)::value, nxt = cur ^ 1;
+        mask_block(cur, j);
+        if (__builtin_expect(__any(smax > kShift), 0)) move_reference(cur, false);   // uniform over the wave, rare
+        float w[16];
+        auto E = [&](int t) __attribute__((always_inline)) { w[t] = __builtin_amdgcn_exp2f(s[cur][t]); };
+        // pack weights 2*e, 2*e+1 of the block (e = 0..7)
+        auto C = [&](int e) __attribute__((always_inline)) { wp[cur][e / 4][e % 4] = pack_f16_rtz(w[2 * e], w[2 * e + 1]); };
+        // running maximum of the scores of block j+1 (registers 4*i .. 4*i+3)
+        auto X = [&](int i) __attribute__((always_inline)) {
+            smax = fmaxf(fmaxf(i == 0 ? s[nxt][0] : smax, s[nxt][4 * i + (i == 0 ? 1 : 0)]),
+                         fmaxf(s[nxt][4 * i + (i == 0 ? 2 : 1)], fmaxf(s[nxt][4 * i + (i == 0 ? 3 : 2)], s[nxt][4 * i + 3])));
+        };
+        SOLAR_FENCE;
+        s[nxt] = mma32(sA[nxt][0], qB[0], cinit);
+        SOLAR_FENCE;
+        E(0); sA[cur][0] = *reinterpret_cast<const v4u*>(sa_next);
+        SOLAR_FENCE;
+        E(1); sA[cur][1] = *reinterpret_cast<const v4u*>(sa_next + 16);
+        SOLAR_FENCE;
+        uint2 zlo, zhi;
+        E(2); zlo = lds_read_tr16(za_this);
+        SOLAR_FENCE;
+        E(3); zhi = lds_read_tr16(za_this + 8 * LDR);
+        SOLAR_FENCE;
+        s[nxt] = mma32(sA[nxt][1], qB[1], s[nxt]);
+        SOLAR_FENCE;
+        E(4); C(0);
+        SOLAR_FENCE;
+        E(5); C(1);
+        SOLAR_FENCE;
+        E(6);
+        SOLAR_FENCE;
+        E(7);
+        SOLAR_FENCE;
+        z = mma32(zA[nxt][0], wp[nxt][0], z);
+        SOLAR_FENCE;
+        zA[cur][0] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
+        E(8); C(2);
+        SOLAR_FENCE;
+        E(9); C(3);
+        SOLAR_FENCE;
+        E(10);
+        SOLAR_FENCE;
+        E(11);
+        SOLAR_FENCE;
+        z = mma32(zA[nxt][1], wp[nxt][1], z);
+        SOLAR_FENCE;
+        lacc = mma32(ones, wp[cur][0], lacc);
+        SOLAR_FENCE;
+        E(12); zlo = lds_read_tr16(za_this + 16 * LDR);
+        SOLAR_FENCE;
+        E(13); zhi = lds_read_tr16(za_this + 24 * LDR);
+        SOLAR_FENCE;
+        E(14); C(4); X(0);
+        SOLAR_FENCE;
+        E(15); C(5); X(1);
+        SOLAR_FENCE;
+        C(6); C(7);
+        zA[cur][1] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
+        SOLAR_FENCE;
+        lacc = mma32(ones, wp[cur][1], lacc);
+        SOLAR_FENCE;
+        X(2); X(3);
+        SOLAR_FENCE;
+    };
+
+    // ---- the sequence loop ---------------------------------------------------------------------
+    const int ntiles = ceil_div(len, kNT);
+    const int nblocks = ceil_div(len, 32);
+    if (ntiles > 0) { fetch(0); commit(tiles, 0); }
+    if (ntiles > 1) { fetch(1); commit(tiles + kBuf, 1); }
+    __syncthreads();
+    if (nblocks > 0) {
+        // S(0) and the reference of the first block; the score operands of block 1
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            sA[0][c] = *reinterpret_cast<const v4u*>(tiles + sa_off + 16 * c);
+            sA[1][c] = *reinterpret_cast<const v4u*>(tiles + 32 * LDR + sa_off + 16 * c);
+        }
+        s[0] = mma32(sA[0][0], qB[0], cinit);
+        s[0] = mma32(sA[0][1], qB[1], s[0]);
+#pragma unroll
+        for (int t = 0; t < 16; ++t) s[1][t] = 0.f;
+        mask_block(0, 0);
+        move_reference(0, true);
+    }
+    using tag0 = std::integral_constant<int, 0>;
+    using tag1 = std::integral_constant<int, 1>;
+    // byte-free rotation of the three tile buffers: element offsets of the tile being
+    // multiplied, the next one and the one being converted
+    int o_cur = 0, o_nxt = kBuf, o_wr = 2 * kBuf;
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const bool ahead = tile + 2 < ntiles;
+        if (__builtin_expect(ahead, 1)) fetch(tile + 2);
+        const uint16_t* sa_cur = tiles + o_cur + sa_off;
+        const uint16_t* sa_nxt = tiles + o_nxt + sa_off;
+        const uint16_t* za_cur = tiles + o_cur + za_off;
+        const int j0 = tile * kNB;
+        slot(j0, tag0{}, sa_cur + 2 * 32 * LDR, za_cur);
+        if (__builtin_expect(j0 + 1 < nblocks, 1)) slot(j0 + 1, tag1{}, sa_cur + 3 * 32 * LDR, za_cur + 32 * LDR);
+        if (__builtin_expect(ahead, 1)) commit(tiles + o_wr, tile + 2);
+        if (__builtin_expect(j0 + 2 < nblocks, 1)) slot(j0 + 2, tag0{}, sa_nxt, za_cur + 2 * 32 * LDR);
+        if (__builtin_expect(j0 + 3 < nblocks, 1)) slot(j0 + 3, tag1{}, sa_nxt + 32 * LDR, za_cur + 3 * 32 * LDR);
+        __syncthreads();
+        const int o = o_cur; o_cur = o_nxt; o_nxt = o_wr; o_wr = o;
+    }
+#undef SOLAR_FENCE
+    // Z of the last block trails the loop
+    if (nblocks > 0) {
+        if ((nblocks - 1) & 1) {
+            z = mma32(zA[1][0], wp[1][0], z);
+            z = mma32(zA[1][1], wp[1][1], z);
+        } else {
+            z = mma32(zA[0][0], wp[0][0], z);
+            z = mma32(zA[0][1], wp[0][1], z);
+        }
+    }
+
+    // ---- epilogue in float: O^T = V (Z / l)^T with the 32x32x2 MFMA: step t contracts the
+    // ranks of register t (one per lane half) -----------------------------------------------------
+    {
+        const float l = lacc[0];
+        const float inv = l > 0.f ? punscale / l : 0.f;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) z[t] *= inv;
+        const int m = m_wave + n32;
+        for (int db = 0; db < D / 32; ++db) {
+            v16f o;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) o[t] = 0.f;
+            const float* vrow = Vs + (32 * db + n32) * LDV + 4 * h;
+#pragma unroll
+            for (int t = 0; t < 16; ++t)
+                o = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[8 * (t / 4) + (t % 4)], z[t], o, 0, 0, 0);
+            if (m < M) {
+                float* orow = O + ((size_t)b * M + m) * D + 32 * db + 4 * h;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<v4f*>(orow + 8 * q) = v4f{o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]};
+            }
+        }
+    }
+}
+
+template <int D>
+hipError_t launch_d(const void* Q, const float* S, const float* V, const float* P, const int32_t* lengths,
+                    int B, int N, int r, int M, float scale, float* O, hipStream_t stream) {
+    const size_t lds = sizeof(float) * (size_t)D * LDV + sizeof(uint16_t) * 3 * (size_t)kBuf;
+    dim3 grid(ceil_div(M, kWaves * kQW) * 8 * ceil_div(B, 8)), block(kThreads);
+    auto kern = attention_seq_x32_kernel<D>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, P, lengths, B, N, r, M, scale, O);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool attention_seq_x32_supported(int d, int r) {
+    return (d == 64 || d == 128 || d == 256) && r >= 4 && r <= 32 && (r % 4) == 0;
+}
+
+// Q is bf16; S must not be null.
+hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* V, const float* P,
+                                    const int32_t* lengths, int B, int N, int d, int r, int M, float scale,
+                                    float* O, hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_d<64>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 128: return launch_d<128>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 256: return launch_d<256>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace solar

@@ -47,6 +47,12 @@ hipError_t launch_attention_seq_bf16(const void* Q, const float* S, const float*
                                      const int32_t* lengths, int B, int N, int d, int r, int M,
                                      float scale, bool split, float* O, hipStream_t stream);
 
+// attention_x32.hip
+bool attention_seq_x32_supported(int d, int r);
+hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* V, const float* P,
+                                    const int32_t* lengths, int B, int N, int d, int r, int M,
+                                    float scale, float* O, hipStream_t stream);
+
 // dense_ref.hip
 hipError_t launch_dense_ref(const void* Q, const void* X, const int32_t* lengths, int B, int N,
                             int d, int M, float scale, bool bf16, float* O, hipStream_t stream);
