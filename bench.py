@@ -26,9 +26,9 @@ N_BUFFER_SETS = 3   # rotate inputs so that X is not served from the 256 MiB Inf
 # profiles/ for the commands and the copy-kernel calibration); keyed by (workload, phase).
 MEASURED_TRAFFIC = {
     # profiles/hbm_traffic_C3.txt: fetch + write bytes of one launch
-    ("C3", "attention"): 99.6e6 + 33.0e6,
-    ("C3", "gram"): 164.1e6 + 18.9e6 + 62.9e6 + 4.2e6,
-    ("C3", "project"): 172.6e6 + 82.7e6,
+    ("C3", "attention"): 99.5e6 + 32.8e6,
+    ("C3", "gram"): 164.1e6 + 9.4e6 + 31.5e6 + 4.2e6,
+    ("C3", "project"): 172.6e6 + 82.5e6,
 }
 
 PEAKS = {
@@ -118,19 +118,30 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
 
-    # latency of one step on its own (no overlap with neighbours), and its phases
-    lat_ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    # Serial pass: the same K steps on one stream, nothing else on the GPU.  Its per-kernel
+    # HIP-event durations are what the roofline figures are taken from (a kernel on its own);
+    # the pipelined pass below gives the throughput.
+    ser_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    ser_start = torch.cuda.Event(enable_timing=True)
+    ser_stop = torch.cuda.Event(enable_timing=True)
     binding.solar_phase_timing_begin()
-    with torch.cuda.stream(streams[0]):
-        lat_ev[0].record()
-        sets[0].factorize()
-        lat_ev[1].record()
-        sets[0].attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
-        lat_ev[2].record()
     torch.cuda.synchronize()
-    _, solo_phase = binding.solar_phase_timing_end()
-    solo = {"gram": solo_phase[0], "eig": solo_phase[1], "project": solo_phase[2],
-            "attention": lat_ev[1].elapsed_time(lat_ev[2]), "step": lat_ev[0].elapsed_time(lat_ev[2])}
+    with torch.cuda.stream(streams[0]):
+        ser_start.record()
+        for i in range(args.steps):
+            db = sets[i % N_BUFFER_SETS]
+            db.factorize()
+            ser_ev[i][0].record()
+            db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
+            ser_ev[i][1].record()
+        ser_stop.record()
+    torch.cuda.synchronize()
+    ser_calls, ser_phase = binding.solar_phase_timing_end()
+    solo = {"gram": ser_phase[0] / max(ser_calls, 1), "eig": ser_phase[1] / max(ser_calls, 1),
+            "project": ser_phase[2] / max(ser_calls, 1),
+            "attention": sum(a.elapsed_time(b) for a, b in ser_ev) / args.steps,
+            "step": ser_start.elapsed_time(ser_stop) / args.steps}
 
     attn_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                for _ in range(args.steps)]
@@ -176,7 +187,8 @@ def main() -> int:
     mfma_peak = PEAKS["mfma_bf16_TFLOPs"] if bf16 else PEAKS["mfma_f32_TFLOPs"]
     kernel_names = {"gram": "gram_partial_kernel (+ gram_finalize_kernel)", "eig": "eig_topr_kernel",
                     "project": "project_bf16_kernel" if bf16 else "project_kernel",
-                    "attention": "attention_seq_bf16_kernel" if bf16 else "attention_seq_kernel"}
+                    "attention": ("attention_seq_x32_kernel" if w.r <= 32 else "attention_seq_bf16_kernel")
+                    if bf16 else "attention_seq_kernel"}
     phases = {"gram": gram_ms, "eig": eig_ms, "project": proj_ms, "attention": attn_ms}
     kernels = {}
     for name, (bound, amount) in work.items():
@@ -191,19 +203,21 @@ def main() -> int:
     kernels["eig"] = {"kernel": kernel_names["eig"], "bound": "latency (serial Jacobi rounds, one "
                       "workgroup per user; no roofline)", "pipelined": {"ms": eig_ms},
                       "alone": {"ms": solo["eig"]}}
-    # dominant kernel = the roofline-bound kernel with the most GPU time in the timed region
-    dominant = max(work, key=lambda k: phases[k])
+    # dominant kernel = the roofline-bound kernel with the most GPU time
+    dominant = max(work, key=lambda k: solo[k])
     traffic = MEASURED_TRAFFIC.get((w.name, dominant))
     roof = {"kernel": kernel_names[dominant], "bound": kernels[dominant]["bound"],
-            "achieved": kernels[dominant]["pipelined"]["achieved"], "peak": kernels[dominant]["peak"],
-            "unit": kernels[dominant]["unit"], "frac": kernels[dominant]["pipelined"]["frac"],
+            "achieved": kernels[dominant]["alone"]["achieved"], "peak": kernels[dominant]["peak"],
+            "unit": kernels[dominant]["unit"], "frac": kernels[dominant]["alone"]["frac"],
             "traffic": traffic,
-            "achieved_alone": kernels[dominant]["alone"]["achieved"],
-            "frac_alone": kernels[dominant]["alone"]["frac"],
-            "note": "durations are HIP-event times inside the timed region, where kernels of "
-                    f"{n_streams} independent batches share the GPU; *_alone is the same launch with "
-                    "nothing else running. eig_topr_kernel has the longest single launch but is "
-                    "latency bound and runs under the other phases."}
+            "achieved_pipelined": kernels[dominant]["pipelined"]["achieved"],
+            "frac_pipelined": kernels[dominant]["pipelined"]["frac"],
+            "note": f"achieved = algorithmic work of one launch / its average HIP-event duration over "
+                    f"the {args.steps} steps of the serial pass (one stream, the kernel has the GPU; "
+                    f"matches `rocprofv3 --kernel-trace --stats -- python bench.py --streams 1`). "
+                    f"*_pipelined is the same over the throughput pass, where kernels of {n_streams} "
+                    "independent batches share the GPU and each launch lasts longer. "
+                    "eig_topr_kernel has the longest single launch but is latency bound (no roofline)."}
 
     out = {
         "metric": "user-sequences/sec (factorize+attend) at N=10k,d=128,r=32,M=1000; % roofline",
@@ -218,7 +232,8 @@ def main() -> int:
                    "recipe": w.recipe, "buffer_sets": N_BUFFER_SETS},
         "phase_ms": phases, "dominant_kernel": dominant, "kernels": kernels,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
-        "streams": n_streams, "single_step_latency_ms": solo,
+        "streams": n_streams, "serial_pass_ms": solo,
+        "value_serial": w.B / (solo["step"] * 1e-3),
         "users_not_converged": info_bad,
         "roofline": roof,
     }

@@ -275,6 +275,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // (a pack or a row sum of the group of exponentials before, an LDS read) issues in its
     // shadow; bunched behind four exponentials those instructions would each cost a slot.
     // sa_next and za_this point at the score operands of block j+2 and the Z operands of block j.
+    // Every MFMA is issued at raised wave priority, so that the matrix unit is fed ahead of the
+    // other wave's vector work.
 #define SOLAR_FENCE __builtin_amdgcn_sched_barrier(0)
     auto slot = [&](int j, auto cur_tag, const uint16_t* sa_next, const uint16_t* za_this)
                     __attribute__((always_inline)) {
@@ -291,7 +293,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
                          fmaxf(s[nxt][4 * i + (i == 0 ? 2 : 1)], fmaxf(s[nxt][4 * i + (i == 0 ? 3 : 2)], s[nxt][4 * i + 3])));
         };
         SOLAR_FENCE;
+        __builtin_amdgcn_s_setprio(1);
         s[nxt] = mma32(sA[nxt][0], qB[0], cinit);
+        __builtin_amdgcn_s_setprio(0);
         SOLAR_FENCE;
         E(0); sA[cur][0] = *reinterpret_cast<const v4u*>(sa_next);
         SOLAR_FENCE;
@@ -302,7 +306,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         SOLAR_FENCE;
         E(3); zhi = lds_read_tr16(za_this + 8 * LDR);
         SOLAR_FENCE;
+        __builtin_amdgcn_s_setprio(1);
         s[nxt] = mma32(sA[nxt][1], qB[1], s[nxt]);
+        __builtin_amdgcn_s_setprio(0);
         SOLAR_FENCE;
         E(4); C(0);
         SOLAR_FENCE;
@@ -312,7 +318,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         SOLAR_FENCE;
         E(7);
         SOLAR_FENCE;
+        __builtin_amdgcn_s_setprio(1);
         z = mma32(zA[nxt][0], wp[nxt][0], z);
+        __builtin_amdgcn_s_setprio(0);
         SOLAR_FENCE;
         zA[cur][0] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
         E(8); C(2);
@@ -323,9 +331,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         SOLAR_FENCE;
         E(11);
         SOLAR_FENCE;
+        __builtin_amdgcn_s_setprio(1);
         z = mma32(zA[nxt][1], wp[nxt][1], z);
+        __builtin_amdgcn_s_setprio(0);
         SOLAR_FENCE;
+        __builtin_amdgcn_s_setprio(1);
         lacc = mma32(ones, wp[cur][0], lacc);
+        __builtin_amdgcn_s_setprio(0);
         SOLAR_FENCE;
         E(12); zlo = lds_read_tr16(za_this + 16 * LDR);
         SOLAR_FENCE;
@@ -338,7 +350,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         C(6); C(7);
         zA[cur][1] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
         SOLAR_FENCE;
+        __builtin_amdgcn_s_setprio(1);
         lacc = mma32(ones, wp[cur][1], lacc);
+        __builtin_amdgcn_s_setprio(0);
         SOLAR_FENCE;
         X(2); X(3);
         SOLAR_FENCE;
