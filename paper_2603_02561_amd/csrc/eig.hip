@@ -5,22 +5,23 @@
 // The iteration is Algorithm 1 expressed on G: a Gaussian start block Omega
 // (d x L, L = r + oversampling), power steps Omega <- X^T (X Omega) = G Omega, an
 // orthonormal basis of the block, and a small decomposition of the projected
-// problem.  Basis and small decomposition are done together by a one-sided
-// (Hestenes) Jacobi method on the d x L block Z = G Q: rotating column pairs of Z
-// until they are mutually orthogonal diagonalizes Q^T G^2 Q, which is the
-// Rayleigh-Ritz step for G^2 on span(Q), and the normalized columns are the next
-// orthonormal basis.  One-sided Jacobi is insensitive to the huge dynamic range of
-// the first block (G Omega is dominated by the leading eigenvectors) and to rank
-// deficiency (columns that vanish are dropped).  Power steps are repeated until
-// every wanted pair (theta_i, q_i) has residual |G q_i - theta_i q_i| below
-// tol_res * theta_max.
+// problem.  On the first power steps only the span of the block matters, and the
+// basis comes from one modified Gram-Schmidt pass.  After those, basis and small
+// decomposition are done together by a one-sided (Hestenes) Jacobi method on the
+// d x L block Z = G Q: rotating column pairs of Z until they are mutually orthogonal
+// diagonalizes Q^T G^2 Q, which is the Rayleigh-Ritz step for G^2 on span(Q), and the
+// normalized columns are the next orthonormal basis.  One-sided Jacobi is insensitive
+// to the huge dynamic range of the block (G Omega is dominated by the leading
+// eigenvectors) and to rank deficiency (columns that vanish are dropped).  The power
+// step after a Jacobi phase yields the residuals |G q_i - theta_i q_i| of the Ritz
+// pairs; the iteration ends when every wanted pair is below tol_res * theta_max, and a
+// failed check doubles the number of Gram-Schmidt steps before the next Jacobi phase.
 //
 // The phase is bound by latency, not by throughput: a Jacobi sweep is L-1 rounds of
 // L/2 independent column rotations with a workgroup barrier after each round.  The
-// kernel therefore runs 16 waves (4 per SIMD) so that LDS latency of one wave hides
-// behind the others, gives every column pair a team of lanes whose partial dot
-// products are combined with DPP lane permutations, and keeps every trip count a
-// compile-time constant.
+// kernel runs eight waves (two per SIMD), gives every column pair a team of up to 16
+// lanes whose partial dot products are combined with DPP lane permutations, and keeps
+// every trip count a compile-time constant.
 #include "common.h"
 #include "kernels.h"
 
