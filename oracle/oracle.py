@@ -126,3 +126,34 @@ def dense_attention(Q, X, scale: float, lengths=None) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"solar_oracle_dense_attention failed: {rc}")
     return O
+
+
+def rsvd_alg1(X, Omega, n_iter: int, lengths=None):
+    """Algorithm 1 ("Randomized SVD with Power Iteration") as printed, in double precision.
+
+    Per user: Omega (d x r, passed in: the Gaussian draw is an input so that the GPU path can
+    use the same one), n_iter times Omega <- H^T (H Omega) with no re-orthonormalisation,
+    Q = orthonormal basis of H Omega by a Householder QR (library routine), the SVD of the small
+    matrix Q^T H (the oracle's own Jacobi SVD), s = its singular values, R = its right
+    singular vectors (sign rule of the oracle: largest-magnitude entry positive).
+    Returns dict(S [B,r], V [B,d,r]).
+    """
+    X = _f64(X)
+    Omega = _f64(Omega)
+    B, N, d = X.shape
+    r = Omega.shape[2]
+    L = _len(lengths)
+    S = np.empty((B, r), dtype=np.float64)
+    V = np.empty((B, d, r), dtype=np.float64)
+    for b in range(B):
+        n = N if L is None else int(L[b])
+        H = X[b, :n]
+        Om = Omega[b].copy()
+        for _ in range(n_iter):
+            Om = H.T @ (H @ Om)
+        Qm, _ = np.linalg.qr(H @ Om, mode="reduced")
+        Bm = Qm.T @ H                               # r x d
+        f = svd_factorize(Bm[None], r)              # singular values and right vectors of Q^T H
+        S[b] = f["S"][0]
+        V[b] = f["V"][0]
+    return dict(S=S, V=V)

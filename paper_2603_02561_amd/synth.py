@@ -164,3 +164,12 @@ def make_config(name: str, users: Optional[Sequence[int]] = None,
         cfg["B"] = B
     seed = SEED0 + 1000 * (int(name[1:]))
     return make_workload(name, seed=seed, users=users, **cfg)
+
+
+def make_omega(B: int, d: int, r: int, seed: int = SEED0 + 77) -> np.ndarray:
+    """Standard normal start blocks Omega [B, d, r] (float32) for the randomized SVD of
+    Algorithm 1, one independent stream per user."""
+    out = np.empty((B, d, r), dtype=np.float32)
+    for b in range(B):
+        out[b] = np.random.default_rng(seed + b).standard_normal((d, r)).astype(np.float32)
+    return out

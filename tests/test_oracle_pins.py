@@ -292,3 +292,75 @@ def test_bad_arguments_are_rejected():
         oracle.svd_factorize(X, 4)        # r > d
     with pytest.raises(RuntimeError):
         oracle.svd_factorize(X, 2, lengths=[1])   # fewer valid rows than r
+
+
+# ---- Algorithm 1 (randomized SVD with power iteration), oracle pins -----------------------------
+
+def _decaying(rng, n, d, rank, decay, noise):
+    U0, _ = np.linalg.qr(rng.standard_normal((n, rank)))
+    V0, _ = np.linalg.qr(rng.standard_normal((d, rank)))
+    sig = 10.0 / np.arange(1, rank + 1) ** decay
+    return (U0 * sig) @ V0.T + noise * rng.standard_normal((n, d))
+
+
+def test_alg1_exact_rank_is_exact_without_power_steps():
+    """On an exactly rank-r matrix the range of H Omega is the range of H almost surely, so
+    Algorithm 1 with n_iter = 0 returns the exact singular values and right subspace."""
+    rng = np.random.default_rng(5)
+    n, d, r = 60, 12, 4
+    X = (rng.standard_normal((n, r)) @ rng.standard_normal((r, d)))[None]
+    Om = rng.standard_normal((1, d, r))
+    got = oracle.rsvd_alg1(X, Om, 0)
+    sv = np.linalg.svd(X[0], compute_uv=True)
+    assert np.allclose(got["S"][0], sv[1][:r], rtol=1e-9, atol=0)
+    Vt = sv[2][:r].T
+    assert np.abs(got["V"][0] @ got["V"][0].T - Vt @ Vt.T).max() < 1e-9
+    assert np.abs(got["V"][0].T @ got["V"][0] - np.eye(r)).max() < 1e-12
+
+
+def test_alg1_singular_values_interlace_and_improve_with_power_steps():
+    """Q^T H is a compression of H: its singular values never exceed those of H (Cauchy
+    interlacing) and the residual of the rank-r reconstruction is bounded below by the
+    Eckart-Young optimum.  On a spectrum with a gap of 0.1 behind sigma_r the subspace converges
+    at the rate (sigma_{r+1}/sigma_r)^(2q+1) of subspace iteration.  (The printed algorithm has
+    no re-orthonormalisation, so q is kept small: sigma_1/sigma_r = 2 here.)"""
+    g = np.random.default_rng(6)
+    n, d, r = 200, 24, 6
+    U0, _ = np.linalg.qr(g.standard_normal((n, 12)))
+    V0, _ = np.linalg.qr(g.standard_normal((d, 12)))
+    sig = np.array([10, 9, 8, 7, 6, 5, 0.5, 0.4, 0.3, 0.2, 0.1, 0.05])
+    X = ((U0 * sig) @ V0.T)[None]
+    Om = g.standard_normal((1, d, r))
+    sv = np.linalg.svd(X[0], compute_uv=True)
+    opt = np.sqrt(np.sum(sv[1][r:] ** 2))
+    Vt = sv[2][:r].T
+    err = {}
+    for q in (0, 1, 2, 3):
+        got = oracle.rsvd_alg1(X, Om, q)
+        assert np.all(got["S"][0] <= sv[1][:r] * (1 + 1e-10))
+        R = got["V"][0]
+        assert np.linalg.norm(X[0] - X[0] @ R @ R.T) >= opt * (1 - 1e-10)
+        err[q] = np.abs(R @ R.T - Vt @ Vt.T).max()
+    assert err[0] > 1e-3                       # one random projection is not the dominant subspace
+    for q in (1, 2, 3):
+        assert err[q] < 20 * 0.1 ** (2 * q + 1)
+    assert np.allclose(got["S"][0], sv[1][:r], rtol=1e-9)
+
+
+def test_alg1_depends_on_omega_only_through_its_range():
+    """Omega -> Omega M (M invertible) leaves range(H Omega) unchanged, hence s and the
+    subspace; a transposed operand anywhere in the chain breaks this."""
+    rng = np.random.default_rng(7)
+    n, d, r = 80, 10, 3
+    X = rng.standard_normal((1, n, d))
+    Om = rng.standard_normal((1, d, r))
+    M = rng.standard_normal((r, r)) + 3 * np.eye(r)
+    a = oracle.rsvd_alg1(X, Om, 0)
+    b = oracle.rsvd_alg1(X, Om @ M, 0)
+    assert np.allclose(a["S"], b["S"], rtol=1e-10)
+    assert np.abs(a["V"][0] @ a["V"][0].T - b["V"][0] @ b["V"][0].T).max() < 1e-10
+    # masked rows are ignored
+    Xp = np.concatenate([X, 7.0 * np.ones((1, 5, d))], axis=1)
+    c = oracle.rsvd_alg1(Xp, Om, 1, lengths=np.array([n], dtype=np.int32))
+    d1 = oracle.rsvd_alg1(X, Om, 1)
+    assert np.allclose(c["S"], d1["S"], rtol=1e-12)
