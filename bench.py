@@ -76,6 +76,9 @@ def main() -> int:
     ap.add_argument("--cpu-users", type=int, default=8)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (reference for PMC byte counters)")
+    ap.add_argument("--alg1", action="store_true",
+                    help="also time the factorization by Algorithm 1 run as printed (passes over X) "
+                         "with 0 and 1 power iterations, next to the Gram route")
     ap.add_argument("--streams", type=int, default=N_BUFFER_SETS,
                     help="independent batches in flight (one HIP stream and one buffer set each)")
     args = ap.parse_args()
@@ -237,6 +240,37 @@ def main() -> int:
         "users_not_converged": info_bad,
         "roofline": roof,
     }
+    if args.alg1:
+        # Algorithm 1 as printed: Y = X Omega, n_iter x (Omega <- X^T Y, Y = X Omega), Q R = Y,
+        # SVD of Q^T X.  Timed one batch at a time; the factors of the Gram route are the reference.
+        db = sets[0]
+        db.factorize()
+        torch.cuda.synchronize()
+        V_ref = db.V.clone()
+        omega = torch.from_numpy(synth.make_omega(w.B, w.d, w.r)).cuda()
+        lens_sum = float(np.sum(lens))
+        alg1 = {}
+        for q in (0, 1):
+            db.factorize_rsvd(omega, q)
+            torch.cuda.synchronize()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            for _ in range(args.steps):
+                db.factorize_rsvd(omega, q)
+            ev1.record()
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1) / args.steps
+            flagged = int((db.info != 0).sum().item())
+            pv = torch.bmm(db.V, db.V.transpose(1, 2)) - torch.bmm(V_ref, V_ref.transpose(1, 2))
+            # bytes the method must move: X (2q+2 passes, + 1 for P), Y written q+1 and read q+1 times, P
+            passes = 2 * q + 2
+            nbytes = (passes + 1) * lens_sum * w.d * e + (2 * (q + 1) + 1) * lens_sum * w.r * 4
+            alg1[f"n_iter={q}"] = {
+                "ms_per_factorize": ms, "passes_over_X": passes + 1, "algorithmic_bytes": nbytes,
+                "achieved_GBps": nbytes / (ms * 1e-3) / 1e9, "users_flagged": flagged,
+                "max_projector_diff_vs_gram_route": float(pv.abs().amax().item())}
+        alg1["gram_route_ms_per_factorize"] = solo["gram"] + solo["eig"] + solo["project"]
+        out["alg1_as_printed"] = alg1
     if not args.no_cpu_baseline:
         n_cpu = min(args.cpu_users, w.B)
         base, o_cpu = cpu_baseline(w, n_cpu)

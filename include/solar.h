@@ -137,6 +137,27 @@ solar_status solar_gram(const void* X, const int32_t* lengths, int B, int N, int
                         void* stream);
 
 /*
+ * The factorization by Algorithm 1 ("Randomized SVD with Power Iteration") run as printed,
+ * with passes over X instead of the Gram matrix: Y = X Omega; n_iter times
+ * Omega <- X^T Y, Y = X Omega (no re-orthonormalisation between power steps); Q R = Y;
+ * s and R = singular values and right singular vectors of Q^T X.  The QR step is carried
+ * by the Cholesky factor of Y^T Y (Q is never formed: Q^T X = R^-T (X^T Y)^T), the small
+ * SVD by a one-sided Jacobi.  X is read 2*n_iter + 2 times (plus once for P).
+ *   Omega    in  [B,d,r] float   the Gaussian start blocks (the caller draws them)
+ *   n_iter   power iterations, >= 0
+ *   S, V, P, info   as for solar_svd_factorize; info[b] = -2 when Y^T Y is not numerically
+ *            positive definite (the columns of Y have collapsed onto the leading singular
+ *            vectors, which the printed algorithm runs into after a few power steps in float)
+ * Supported: d in {64, 128}, r in {16, 32, 48, 64}, r <= d.  Workspace:
+ * solar_rsvd_workspace_bytes(B, N, d, r) bytes, 256-byte aligned.
+ */
+size_t solar_rsvd_workspace_bytes(int B, int N, int d, int r);
+solar_status solar_svd_factorize_rsvd(const void* X, const int32_t* lengths, int B, int N, int d,
+                                      int r, solar_dtype t, const float* Omega, int n_iter,
+                                      float* S, float* V, float* P, int32_t* info,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Per-phase timing of solar_svd_factorize, for benchmarks.  After
  * solar_phase_timing_begin() every factorize call (up to 256 of them) records HIP
  * events on its stream around its three phases: the Gram contraction, the

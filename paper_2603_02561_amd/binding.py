@@ -43,6 +43,11 @@ _lib.solar_svd_attention.restype = _ci
 _lib.solar_dense_attention_ref.argtypes = [_vp, _vp, _vp, _ci, _ci, _ci, _ci, _cf, _ci, _vp, _vp,
                                            _sz, _vp]
 _lib.solar_dense_attention_ref.restype = _ci
+_lib.solar_rsvd_workspace_bytes.argtypes = [_ci, _ci, _ci, _ci]
+_lib.solar_rsvd_workspace_bytes.restype = _sz
+_lib.solar_svd_factorize_rsvd.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _vp, _vp, _vp,
+                                          _vp, _vp, _sz, _vp]
+_lib.solar_svd_factorize_rsvd.restype = _ci
 _lib.solar_phase_timing_begin.argtypes = []
 _lib.solar_phase_timing_begin.restype = None
 _lib.solar_phase_timing_end.argtypes = [ctypes.POINTER(ctypes.c_float)]
@@ -118,6 +123,23 @@ def solar_svd_factorize(X, lengths, r: int, S, V, P, info, workspace,
     return rc
 
 
+def solar_rsvd_workspace_bytes(B: int, N: int, d: int, r: int) -> int:
+    return int(_lib.solar_rsvd_workspace_bytes(B, N, d, r))
+
+
+def solar_svd_factorize_rsvd(X, lengths, r: int, Omega, n_iter: int, S, V, P, info, workspace,
+                             raise_on_error: bool = True) -> int:
+    _check(X, lengths, Omega, S, V, P, info, workspace)
+    B, N, d = X.shape
+    rc = _lib.solar_svd_factorize_rsvd(_ptr(X), _ptr(lengths), B, N, d, int(r), _dtype_code(X),
+                                       _ptr(Omega), int(n_iter), _ptr(S), _ptr(V), _ptr(P), _ptr(info),
+                                       _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                       _stream())
+    if rc != SOLAR_OK and raise_on_error:
+        raise SolarError(rc)
+    return rc
+
+
 def solar_svd_attention(Q, S, V, P, lengths, N: int, scale: float, mode: int, O, workspace=None,
                         raise_on_error: bool = True) -> int:
     _check(Q, S, V, P, lengths, O, workspace)
@@ -176,6 +198,15 @@ class DeviceBatch:
     def factorize(self):
         return solar_svd_factorize(self.X, self.lengths, self.r, self.S, self.V, self.P, self.info,
                                    self.workspace)
+
+    def factorize_rsvd(self, Omega, n_iter: int):
+        """Algorithm 1 as printed (passes over X); Omega is a [B,d,r] float device tensor."""
+        if getattr(self, "rsvd_workspace", None) is None:
+            nbytes = solar_rsvd_workspace_bytes(self.B, self.N, self.d, self.r)
+            self.rsvd_workspace = torch.empty((max(nbytes, 256),), dtype=torch.uint8,
+                                              device=self.X.device)
+        return solar_svd_factorize_rsvd(self.X, self.lengths, self.r, Omega, n_iter, self.S, self.V,
+                                        self.P, self.info, self.rsvd_workspace)
 
     def attention(self, scale: float, mode: int = SOLAR_ATTN_SEQ_SOFTMAX, O=None):
         return solar_svd_attention(self.Q, self.S, self.V, self.P, self.lengths, self.N, scale,

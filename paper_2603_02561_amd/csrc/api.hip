@@ -148,6 +148,50 @@ solar_status solar_svd_factorize(const void* X, const int32_t* lengths, int B, i
     return SOLAR_OK;
 }
 
+size_t solar_rsvd_workspace_bytes(int B, int N, int d, int r) {
+    if (B <= 0 || N <= 0 || d <= 0 || r <= 0 || !rsvd_supported(d, r)) return 0;
+    return align256(sizeof(float) * (size_t)B * N * r) + align256(sizeof(float) * (size_t)B * d * r) +
+           align256(sizeof(float) * (size_t)B * r * r) + align256(sizeof(float) * xty_partial_floats(B, N, d, r));
+}
+
+solar_status solar_svd_factorize_rsvd(const void* X, const int32_t* lengths, int B, int N, int d, int r,
+                                      solar_dtype t, const float* Omega, int n_iter, float* S, float* V,
+                                      float* P, int32_t* info, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+    if (!X || !Omega || !S || !V || B <= 0 || N <= 0 || d <= 0 || r <= 0 || n_iter < 0) return SOLAR_ERR_INVALID_ARG;
+    if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
+    if (r > d || r > N) return SOLAR_ERR_INVALID_ARG;
+    if (!rsvd_supported(d, r)) return SOLAR_ERR_UNSUPPORTED;
+    const size_t need = solar_rsvd_workspace_bytes(B, N, d, r);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return SOLAR_ERR_WORKSPACE;
+    char* base = static_cast<char*>(workspace);
+    float* Y = reinterpret_cast<float*>(base);
+    base += align256(sizeof(float) * (size_t)B * N * r);
+    float* Wb = reinterpret_cast<float*>(base);
+    base += align256(sizeof(float) * (size_t)B * d * r);
+    float* Gy = reinterpret_cast<float*>(base);
+    base += align256(sizeof(float) * (size_t)B * r * r);
+    float* partials = reinterpret_cast<float*>(base);
+    hipStream_t st = (hipStream_t)stream;
+    const bool bf16 = t == SOLAR_BF16;
+    hipError_t e = launch_project(X, lengths, Omega, nullptr, B, N, d, r, bf16, Y, st);
+    if (e != hipSuccess) return SOLAR_ERR_HIP;
+    for (int it = 0; it <= n_iter; ++it) {
+        e = launch_xty(X, Y, lengths, B, N, d, r, bf16, partials, Wb, Gy, st);
+        if (e != hipSuccess) return SOLAR_ERR_HIP;
+        if (it == n_iter) break;
+        e = launch_project(X, lengths, Wb, nullptr, B, N, d, r, bf16, Y, st);
+        if (e != hipSuccess) return SOLAR_ERR_HIP;
+    }
+    e = launch_rsvd_small(Wb, Gy, lengths, B, N, d, r, S, V, info, st);
+    if (e != hipSuccess) return SOLAR_ERR_HIP;
+    if (P) {
+        e = launch_project(X, lengths, V, info, B, N, d, r, bf16, P, st);
+        if (e != hipSuccess) return SOLAR_ERR_HIP;
+    }
+    return SOLAR_OK;
+}
+
 solar_status solar_svd_attention(const void* Q, const float* S, const float* V, const float* P,
                                  const int32_t* lengths, int B, int N, int d, int r, int M,
                                  float scale, solar_attn_mode mode, solar_dtype t, float* O,

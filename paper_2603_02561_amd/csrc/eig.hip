@@ -410,6 +410,144 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     }
 }
 
+// Last step of Algorithm 1 when it is run with passes over H: from W = H^T Y (d x r) and
+// Gy = Y^T Y (r x r) of the final Y = H Omega, the QR factor R of Y is the Cholesky factor of
+// Gy (Y = Q R  =>  Gy = R^T R), Q^T H = R^-T W^T, and the singular values s and right singular
+// vectors of Q^T H are the column norms and normalized columns of (Q^T H)^T = W R^-1 once a
+// one-sided Jacobi has made those columns mutually orthogonal.  One workgroup per user, all of
+// it in LDS.  info: 0 ok, > 0 Jacobi sweeps exhausted, -1 bad length, -2 Gy is not numerically
+// positive definite (the columns of Y have collapsed, as they do after too many power steps
+// without re-orthonormalisation).
+template <int D, int L>
+__global__ __launch_bounds__(kEigThreads) void rsvd_small_kernel(
+    const float* __restrict__ W, const float* __restrict__ Gy, const int32_t* __restrict__ lengths, int N,
+    float* __restrict__ S, float* __restrict__ V, int32_t* __restrict__ info, int max_sweeps) {
+    using C = EigCfg<D, L>;
+    constexpr int LP = C::LP, LD = C::LD, TC = C::TC, LR = L + 1;
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float* Zc = smem;                  // [LP][LD] columns of W R^-1
+    float* Rm = Zc + LP * LD;          // [L][LR] Gy, then its Cholesky factor (upper triangle)
+    float* nrm = Rm + L * LR;          // [LP] column norms
+    int* rankv = reinterpret_cast<int*>(nrm + LP);   // [LP]
+    __shared__ int sh_bad;
+    __shared__ int sh_bits;
+    const int tid = threadIdx.x, b = blockIdx.x;
+    const int r = L;
+    auto fail = [&](int code) {
+        for (int e = tid; e < D * r; e += kEigThreads) V[(size_t)b * D * r + e] = 0.f;
+        for (int e = tid; e < r; e += kEigThreads) S[(size_t)b * r + e] = 0.f;
+        if (tid == 0 && info) info[b] = code;
+    };
+    {
+        const int raw = lengths ? lengths[b] : N;
+        if (raw < r || raw > N) { fail(-1); return; }   // uniform over the workgroup
+    }
+    if (tid == 0) { sh_bad = 0; sh_bits = 0; }
+    for (int e = tid; e < L * L; e += kEigThreads) Rm[(e / L) * LR + e % L] = Gy[(size_t)b * L * L + e];
+    for (int e = tid; e < LP * LD; e += kEigThreads) Zc[e] = 0.f;
+    __syncthreads();
+    // Cholesky, right-looking.  A pivot below 1e-5 of its diagonal entry counts as breakdown:
+    // the results would carry a relative error of about 2^-24 / 1e-5, a percent.
+    for (int k = 0; k < L; ++k) {
+        const float piv = Rm[k * LR + k];
+        const float d0 = Gy[(size_t)b * L * L + k * L + k];
+        if (!(piv > 1.0e-5f * d0) || !(piv > 0.f)) { if (tid == 0) sh_bad = 1; }
+        __syncthreads();
+        if (sh_bad) break;   // uniform
+        const float rkk = __builtin_amdgcn_sqrtf(piv);
+        const float inv = 1.f / rkk;
+        __syncthreads();
+        for (int jx = k + tid; jx < L; jx += kEigThreads) Rm[k * LR + jx] = (jx == k) ? rkk : Rm[k * LR + jx] * inv;
+        __syncthreads();
+        const int m = L - k - 1;
+        for (int e = tid; e < m * m; e += kEigThreads) {
+            const int i = k + 1 + e / m, jx = k + 1 + e % m;
+            if (jx >= i) Rm[i * LR + jx] -= Rm[k * LR + i] * Rm[k * LR + jx];
+        }
+        __syncthreads();
+    }
+    if (sh_bad) { fail(-2); return; }
+    // rows of W R^-1 by forward substitution, one thread per row
+    for (int a = tid; a < D; a += kEigThreads) {
+        float x[L];
+        const float* w = W + ((size_t)b * D + a) * L;
+#pragma unroll
+        for (int jx = 0; jx < L; ++jx) {
+            float acc = w[jx];
+#pragma unroll
+            for (int i = 0; i < jx; ++i) acc -= x[i] * Rm[i * LR + jx];
+            x[jx] = acc / Rm[jx * LR + jx];
+            Zc[jx * LD + a] = x[jx];
+        }
+    }
+    __syncthreads();
+    const int col = tid / TC, cu = tid % TC;
+    auto column_norms = [&]() {
+        if (col < L) {
+            const float* z = Zc + col * LD;
+            float nn = 0.f;
+            for (int i = cu; i < D; i += TC) nn += z[i] * z[i];
+            nn = team_sum<TC>(nn);
+            if (cu == 0) { nrm[col] = nn; atomicMax(&sh_bits, __float_as_int(nn)); }
+        }
+        __syncthreads();
+    };
+    column_norms();
+    const float dead2 = kDeadRel * kDeadRel * __int_as_float(sh_bits);
+    int status = max_sweeps;
+    for (int sw = 0; sw < max_sweeps; ++sw) {
+        const float mine = jacobi_sweep<D, L>(Zc, dead2);
+        const bool any = __syncthreads_or(mine > kSweepDone);
+        if (!any) { status = 0; break; }
+    }
+    column_norms();
+    if (tid < L) {
+        const float th = nrm[tid];
+        int rk = 0;
+        for (int k = 0; k < L; ++k) {
+            const float tk = nrm[k];
+            rk += (tk > th || (tk == th && k < tid)) ? 1 : 0;
+        }
+        rankv[tid] = rk;
+    }
+    __syncthreads();
+    // outputs: columns ranked by norm, sign fixed by the largest-magnitude entry
+    if (col < L) {
+        const int k = rankv[col];
+        const float nn = nrm[col];
+        const float inv = nn > 0.f ? __builtin_amdgcn_rsqf(nn) : 0.f;
+        const float* q = Zc + col * LD;
+        float best = -1.f;
+        int bi = 0;
+        for (int i = cu; i < D; i += TC) {
+            const float a = fabsf(q[i]);
+            if (a > best) { best = a; bi = i; }
+        }
+        for (int m = 1; m < TC; m <<= 1) {
+            const float ob = __shfl_xor(best, m);
+            const int oi = __shfl_xor(bi, m);
+            if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
+        }
+        const float sgn = (q[bi] < 0.f) ? -inv : inv;
+        for (int i = cu; i < D; i += TC) V[((size_t)b * D + i) * r + k] = sgn * q[i];
+        if (cu == 0) S[(size_t)b * r + k] = __builtin_amdgcn_sqrtf(nn);
+    }
+    if (tid == 0 && info) info[b] = status;
+}
+
+template <int D, int L>
+hipError_t launch_rsvd_small_t(const float* W, const float* Gy, const int32_t* lengths, int B, int N,
+                               float* S, float* V, int32_t* info, hipStream_t stream) {
+    using C = EigCfg<D, L>;
+    const size_t lds = sizeof(float) * ((size_t)C::LP * C::LD + (size_t)L * (L + 1) + 2 * C::LP + 8);
+    auto kern = rsvd_small_kernel<D, L>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(B), dim3(kEigThreads), lds, stream, W, Gy, lengths, N, S, V, info, 30);
+    return hipGetLastError();
+}
+
 template <int D, int L>
 hipError_t launch_eig_t(const float* G, const int32_t* lengths, int B, int N, int r, float* S,
                         float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
@@ -482,6 +620,16 @@ hipError_t launch_eig(const float* G, const int32_t* lengths, int B, int N, int 
         case 256: return launch_eig_d<256>(G, lengths, B, N, r, S, V, info, prm, stream);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_rsvd_small(const float* W, const float* Gy, const int32_t* lengths, int B, int N, int d,
+                             int r, float* S, float* V, int32_t* info, hipStream_t stream) {
+#define SOLAR_RSVD_CASE(DD, LL) \
+    if (d == DD && r == LL) return launch_rsvd_small_t<DD, LL>(W, Gy, lengths, B, N, S, V, info, stream);
+    SOLAR_RSVD_CASE(64, 16) SOLAR_RSVD_CASE(64, 32) SOLAR_RSVD_CASE(64, 48) SOLAR_RSVD_CASE(64, 64)
+    SOLAR_RSVD_CASE(128, 16) SOLAR_RSVD_CASE(128, 32) SOLAR_RSVD_CASE(128, 48) SOLAR_RSVD_CASE(128, 64)
+#undef SOLAR_RSVD_CASE
+    return hipErrorInvalidValue;
 }
 
 }  // namespace solar

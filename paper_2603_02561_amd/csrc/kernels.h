@@ -28,6 +28,15 @@ size_t eig_lds_bytes(int d, int r);
 hipError_t launch_eig(const float* G, const int32_t* lengths, int B, int N, int d, int r, float* S,
                       float* V, int32_t* info, const EigParams& prm, hipStream_t stream);
 
+hipError_t launch_rsvd_small(const float* W, const float* Gy, const int32_t* lengths, int B, int N, int d,
+                             int r, float* S, float* V, int32_t* info, hipStream_t stream);
+
+// rsvd.hip
+bool rsvd_supported(int d, int r);
+size_t xty_partial_floats(int B, int N, int d, int r);
+hipError_t launch_xty(const void* X, const float* Y, const int32_t* lengths, int B, int N, int d, int r,
+                      bool bf16, float* partials, float* W, float* Gy, hipStream_t stream);
+
 // project.hip
 hipError_t launch_project(const void* X, const int32_t* lengths, const float* V,
                           const int32_t* info, int B, int N, int d, int r, bool bf16, float* P,
