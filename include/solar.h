@@ -127,6 +127,30 @@ solar_status solar_dense_attention_ref(const void* Q, const void* X, const int32
                                        void* stream);
 
 /*
+ * Linear attention of the Preliminaries, Attn_lin = Query (Key^T Value) with Key = Value = X:
+ * O_b = scale * Q_b (X_b^T X_b) over the valid rows of X_b, no softmax.  It is the operator the
+ * paper compares against in its forward-latency figure, and what the literal r-token mode
+ * (SOLAR_ATTN_LINEAR) truncates to rank r.  Workspace: solar_workspace_bytes(...).
+ *   O        out [B,M,d] float
+ */
+solar_status solar_linear_attention(const void* Q, const void* X, const int32_t* lengths, int B, int N,
+                                    int d, int M, float scale, solar_dtype t, float* O,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The learnable projections of the Preliminaries (Query = C W_Q, Key = H W_K, Value = H W_V)
+ * folded around an operator that works on H itself: Out = In * W for every row, W a d x d float
+ * matrix shared by all rows.  With Wfold = W_Q W_K^T applied to the candidates before
+ * solar_svd_attention and W_V applied to its output, every mode equals the operator with the
+ * projections inside, because Key and Value share H.
+ *   In       [rows, d]   element type t_in
+ *   W        [d, d] float, row-major
+ *   Out      [rows, d]   element type t_out (bf16 output is rounded to nearest even)
+ */
+solar_status solar_apply_weights(const void* In, const float* W, int rows, int d, solar_dtype t_in,
+                                 solar_dtype t_out, void* Out, void* stream);
+
+/*
  * First phase of the factorization on its own, exported so that it can be checked
  * and profiled in isolation: G_b = X_b^T X_b over the valid rows, the contraction
  * over the sequence axis that Algorithm 1's power iteration applies to Omega.

@@ -157,3 +157,23 @@ def rsvd_alg1(X, Omega, n_iter: int, lengths=None):
         S[b] = f["S"][0]
         V[b] = f["V"][0]
     return dict(S=S, V=V)
+
+
+def linear_attention(Q, X, scale: float, lengths=None) -> np.ndarray:
+    """Attn_lin = Query (Key^T Value) of the Preliminaries with Key = Value = X (W = I):
+    O_b = scale * Q_b (X_b^T X_b) over the valid rows, evaluated in that order."""
+    Q = _f64(Q)
+    X = _f64(X)
+    L = _len(lengths)
+    B, N, _ = X.shape
+    O = np.empty_like(Q)
+    for b in range(B):
+        n = N if L is None else int(L[b])
+        H = X[b, :n]
+        O[b] = scale * (Q[b] @ (H.T @ H))
+    return O
+
+
+def apply_weights(In, W) -> np.ndarray:
+    """Rows times a shared d x d matrix: the projections Query = C W_Q etc. of the Preliminaries."""
+    return _f64(In) @ _f64(W)

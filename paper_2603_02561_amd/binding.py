@@ -48,6 +48,10 @@ _lib.solar_rsvd_workspace_bytes.restype = _sz
 _lib.solar_svd_factorize_rsvd.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _vp, _vp, _vp,
                                           _vp, _vp, _sz, _vp]
 _lib.solar_svd_factorize_rsvd.restype = _ci
+_lib.solar_linear_attention.argtypes = [_vp, _vp, _vp, _ci, _ci, _ci, _ci, _cf, _ci, _vp, _vp, _sz, _vp]
+_lib.solar_linear_attention.restype = _ci
+_lib.solar_apply_weights.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp]
+_lib.solar_apply_weights.restype = _ci
 _lib.solar_phase_timing_begin.argtypes = []
 _lib.solar_phase_timing_begin.restype = None
 _lib.solar_phase_timing_end.argtypes = [ctypes.POINTER(ctypes.c_float)]
@@ -167,6 +171,29 @@ def solar_dense_attention_ref(Q, X, lengths, scale: float, O, workspace=None,
     return rc
 
 
+def solar_linear_attention(Q, X, lengths, scale: float, O, workspace, raise_on_error: bool = True) -> int:
+    _check(Q, X, lengths, O, workspace)
+    B, M, d = Q.shape
+    N = X.shape[1]
+    rc = _lib.solar_linear_attention(_ptr(Q), _ptr(X), _ptr(lengths), B, N, d, M, float(scale),
+                                     _dtype_code(Q), _ptr(O), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream())
+    if rc != SOLAR_OK and raise_on_error:
+        raise SolarError(rc)
+    return rc
+
+
+def solar_apply_weights(In, W, Out, raise_on_error: bool = True) -> int:
+    _check(In, W, Out)
+    d = In.shape[-1]
+    rows = In.numel() // d
+    rc = _lib.solar_apply_weights(_ptr(In), _ptr(W), rows, d, _dtype_code(In), _dtype_code(Out), _ptr(Out),
+                                  _stream())
+    if rc != SOLAR_OK and raise_on_error:
+        raise SolarError(rc)
+    return rc
+
+
 # ---------------------------------------------------------------------------------------
 # Convenience for tests and the benchmark: device buffers for one workload.
 
@@ -211,6 +238,10 @@ class DeviceBatch:
     def attention(self, scale: float, mode: int = SOLAR_ATTN_SEQ_SOFTMAX, O=None):
         return solar_svd_attention(self.Q, self.S, self.V, self.P, self.lengths, self.N, scale,
                                    mode, self.O if O is None else O, self.workspace)
+
+    def linear(self, scale: float, O=None):
+        return solar_linear_attention(self.Q, self.X, self.lengths, scale, self.O if O is None else O,
+                                      self.workspace)
 
     def dense(self, scale: float, O=None):
         return solar_dense_attention_ref(self.Q, self.X, self.lengths, scale,

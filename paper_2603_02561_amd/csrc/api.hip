@@ -192,6 +192,33 @@ solar_status solar_svd_factorize_rsvd(const void* X, const int32_t* lengths, int
     return SOLAR_OK;
 }
 
+solar_status solar_linear_attention(const void* Q, const void* X, const int32_t* lengths, int B, int N,
+                                    int d, int M, float scale, solar_dtype t, float* O, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    if (!Q || !X || !O || B <= 0 || N <= 0 || d <= 0 || M <= 0) return SOLAR_ERR_INVALID_ARG;
+    if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
+    if (d != 64 && d != 128 && d != 256) return SOLAR_ERR_UNSUPPORTED;
+    Carve c = carve(workspace, B, N, d);
+    if (!workspace || workspace_bytes < c.total || ((uintptr_t)workspace & 255)) return SOLAR_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const bool bf16 = t == SOLAR_BF16;
+    hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, st);
+    if (e != hipSuccess) return SOLAR_ERR_HIP;
+    e = launch_rowgemm(Q, c.G, (size_t)d * d, B, M, d, scale, bf16, false, O, st);
+    return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
+}
+
+solar_status solar_apply_weights(const void* In, const float* W, int rows, int d, solar_dtype t_in,
+                                 solar_dtype t_out, void* Out, void* stream) {
+    if (!In || !W || !Out || rows <= 0 || d <= 0) return SOLAR_ERR_INVALID_ARG;
+    if ((t_in != SOLAR_F32 && t_in != SOLAR_BF16) || (t_out != SOLAR_F32 && t_out != SOLAR_BF16))
+        return SOLAR_ERR_INVALID_ARG;
+    if (d != 64 && d != 128 && d != 256) return SOLAR_ERR_UNSUPPORTED;
+    hipError_t e = launch_rowgemm(In, W, 0, 1, rows, d, 1.f, t_in == SOLAR_BF16, t_out == SOLAR_BF16, Out,
+                                  (hipStream_t)stream);
+    return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
+}
+
 solar_status solar_svd_attention(const void* Q, const float* S, const float* V, const float* P,
                                  const int32_t* lengths, int B, int N, int d, int r, int M,
                                  float scale, solar_attn_mode mode, solar_dtype t, float* O,

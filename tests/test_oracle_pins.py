@@ -364,3 +364,37 @@ def test_alg1_depends_on_omega_only_through_its_range():
     c = oracle.rsvd_alg1(Xp, Om, 1, lengths=np.array([n], dtype=np.int32))
     d1 = oracle.rsvd_alg1(X, Om, 1)
     assert np.allclose(c["S"], d1["S"], rtol=1e-12)
+
+
+# ---- linear attention and folded projections ------------------------------------------------------
+
+def test_linear_attention_is_attention_without_softmax_and_full_rank_mode2():
+    """Query (Key^T Value) equals (Query Key^T) Value (associativity: the dense operator with the
+    softmax removed), and equals the r-token form without softmax at r = d, where the
+    truncation is void (Section SVD-Attention, identity X^T X = V S^2 V^T)."""
+    g = rng(31)
+    X = g.standard_normal((2, 50, 6))
+    Q = g.standard_normal((2, 7, 6))
+    lengths = np.array([50, 33], dtype=np.int32)
+    got = oracle.linear_attention(Q, X, 0.7, lengths)
+    for b in range(2):
+        n = lengths[b]
+        want = 0.7 * (Q[b] @ X[b, :n].T) @ X[b, :n]
+        assert np.allclose(got[b], want, rtol=1e-12, atol=1e-12)
+    f = oracle.svd_factorize(X, 6, lengths)
+    mode2 = oracle.svd_attention(Q, None, f["S"], f["V"], 0.7, 2)
+    assert np.allclose(got, mode2, rtol=1e-9, atol=1e-9)
+
+
+def test_folded_projections_equal_projections_inside():
+    """With Key = H W_K and Value = H W_V the linear operator is
+    C W_Q (W_K^T H^T H W_V) = [C (W_Q W_K^T)] (H^T H) W_V: folding W_Q W_K^T into the candidates and
+    W_V into the output reproduces the projections applied inside."""
+    g = rng(32)
+    H = g.standard_normal((1, 40, 5))
+    C = g.standard_normal((1, 9, 5))
+    WQ, WK, WV = (g.standard_normal((5, 5)) for _ in range(3))
+    inside = (C[0] @ WQ) @ ((H[0] @ WK).T @ (H[0] @ WV))
+    folded = oracle.apply_weights(
+        oracle.linear_attention(oracle.apply_weights(C, WQ @ WK.T), H, 1.0), WV)[0]
+    assert np.allclose(inside, folded, rtol=1e-10, atol=1e-10)
