@@ -66,6 +66,60 @@ def cpu_baseline(w, n_users: int):
     }, np.concatenate(outs, axis=0)
 
 
+def latency_sweep(w, steps: int):
+    """Forward latency against the history length N at fixed B, M, d, r (Section "Forward-pass
+    efficiency of attention"): softmax attention (the correctness-first dense reference kernel, not
+    tuned), linear attention Q (X^T X), SVD-attention with the factorization inside and with the
+    factors reused.  CPU figures: the oracle on one thread, one user, at the shorter lengths."""
+    import numpy as np
+    import torch
+    from paper_2603_02561_amd import binding, synth
+    from oracle import oracle
+
+    def gpu_ms(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    rows = []
+    for n in (1000, 2000, 5000, 10000, 20000):
+        wl = synth.make_workload(f"sweep{n}", w.B, n, w.d, w.r, w.M, w.dtype, "spectrum", 1.0, 0.01,
+                                 seed=4242 + n)
+        db = binding.DeviceBatch(wl.X, wl.Q, wl.lengths, wl.r, wl.dtype == synth.BF16)
+        row = {"N": n, "B": w.B, "M": w.M, "d": w.d, "r": w.r}
+
+        def svd_full():
+            db.factorize()
+            db.attention(1.0, binding.SOLAR_ATTN_SEQ_SOFTMAX)
+        row["gpu_ms_svd_attention"] = gpu_ms(svd_full, steps)
+        row["gpu_ms_svd_attention_factors_reused"] = gpu_ms(
+            lambda: db.attention(1.0, binding.SOLAR_ATTN_SEQ_SOFTMAX), steps)
+        row["gpu_ms_linear_attention"] = gpu_ms(lambda: db.linear(1.0), steps)
+        row["gpu_ms_softmax_attention_reference_kernel"] = gpu_ms(lambda: db.dense(1.0), max(1, steps // 5))
+        if n <= 2000:
+            X1, Q1 = wl.X[:1], wl.Q[:1]
+            t0 = time.perf_counter()
+            f = oracle.svd_factorize(X1, wl.r)
+            oracle.svd_attention(Q1, X1, f["S"], f["V"], 1.0, 0)
+            t1 = time.perf_counter()
+            oracle.linear_attention(Q1, X1, 1.0)
+            t2 = time.perf_counter()
+            oracle.dense_attention(Q1, X1, 1.0)
+            t3 = time.perf_counter()
+            row["cpu_1thread_ms_per_user"] = {"svd_attention_oracle": (t1 - t0) * 1e3,
+                                              "linear_attention_oracle": (t2 - t1) * 1e3,
+                                              "softmax_attention_oracle": (t3 - t2) * 1e3}
+        rows.append(row)
+        del db
+    return rows
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +133,10 @@ def main() -> int:
     ap.add_argument("--alg1", action="store_true",
                     help="also time the factorization by Algorithm 1 run as printed (passes over X) "
                          "with 0 and 1 power iterations, next to the Gram route")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also sweep the history length N at fixed M, d, r (the protocol of the paper's "
+                         "forward-latency figure): softmax, linear and SVD attention on the GPU, and the "
+                         "oracle on one CPU thread at the shorter lengths")
     ap.add_argument("--streams", type=int, default=N_BUFFER_SETS,
                     help="independent batches in flight (one HIP stream and one buffer set each)")
     args = ap.parse_args()
@@ -271,6 +329,8 @@ def main() -> int:
                 "max_projector_diff_vs_gram_route": float(pv.abs().amax().item())}
         alg1["gram_route_ms_per_factorize"] = solo["gram"] + solo["eig"] + solo["project"]
         out["alg1_as_printed"] = alg1
+    if args.sweep:
+        out["sweep"] = latency_sweep(w, args.steps)
     if not args.no_cpu_baseline:
         n_cpu = min(args.cpu_users, w.B)
         base, o_cpu = cpu_baseline(w, n_cpu)
