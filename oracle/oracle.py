@@ -177,3 +177,33 @@ def linear_attention(Q, X, scale: float, lengths=None) -> np.ndarray:
 def apply_weights(In, W) -> np.ndarray:
     """Rows times a shared d x d matrix: the projections Query = C W_Q etc. of the Preliminaries."""
     return _f64(In) @ _f64(W)
+
+
+def svd_backward(X, r: int, S_bar, V_bar, lengths=None, gap_rel: float = 0.0) -> np.ndarray:
+    """Gradient of a loss through the truncated SVD with respect to X ("Backward Pass Through
+    SVD", the form with U-bar = 0): dL/dX = U [diag(S_bar) + 2 S sym(F o (V^T V_bar))] V^T with
+    sym(A) = (A + A^T)/2 and F_ij = 1/(s_j^2 - s_i^2) off the diagonal, 0 on it -- the orientation
+    of F that central finite differences confirm (the printed F_ij = 1/(s_i^2 - s_j^2) is its
+    transpose).  Pairs with |s_i^2 - s_j^2| <= gap_rel * s_1^2 get F_ij = 0.  U, S, V come from the
+    oracle's own Jacobi SVD.  Rows past the valid length get zero gradient."""
+    X = _f64(X)
+    S_bar = _f64(S_bar)
+    V_bar = _f64(V_bar)
+    B, N, d = X.shape
+    L = _len(lengths)
+    f = svd_factorize(X, r, lengths, want_u=True)
+    dX = np.zeros_like(X)
+    for b in range(B):
+        n = N if L is None else int(L[b])
+        U, S, V = f["U"][b, :n], f["S"][b], f["V"][b]
+        A = V.T @ V_bar[b]
+        s2 = S * S
+        diff = s2[None, :] - s2[:, None]                 # [i, j] = s_j^2 - s_i^2
+        F = np.zeros((r, r))
+        ok = np.abs(diff) > gap_rel * s2[0]
+        np.fill_diagonal(ok, False)
+        F[ok] = 1.0 / diff[ok]
+        Bm = F * A
+        K = np.diag(S_bar[b]) + 2.0 * np.diag(S) @ (0.5 * (Bm + Bm.T))
+        dX[b, :n] = U @ K @ V.T
+    return dX

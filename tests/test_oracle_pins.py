@@ -398,3 +398,56 @@ def test_folded_projections_equal_projections_inside():
     folded = oracle.apply_weights(
         oracle.linear_attention(oracle.apply_weights(C, WQ @ WK.T), H, 1.0), WV)[0]
     assert np.allclose(inside, folded, rtol=1e-10, atol=1e-10)
+
+
+# ---- SVD backward -----------------------------------------------------------------------------------
+
+def _svd_loss(X, r, S_bar, V_bar):
+    f = oracle.svd_factorize(X[None], r)
+    return float(np.sum(S_bar * f["S"][0]) + np.sum(V_bar * f["V"][0]))
+
+
+def _fd_grad(X, r, S_bar, V_bar, h=1e-6):
+    g = np.zeros_like(X)
+    for i in range(X.shape[0]):
+        for j in range(X.shape[1]):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[i, j] += h
+            Xm[i, j] -= h
+            g[i, j] = (_svd_loss(Xp, r, S_bar, V_bar) - _svd_loss(Xm, r, S_bar, V_bar)) / (2 * h)
+    return g
+
+
+def test_svd_backward_matches_finite_differences_full_rank():
+    """r = d: the formula is the whole gradient of <S_bar, S> + <V_bar, V> (nothing of V_bar lies
+    outside span(V)); central differences through the oracle's own SVD fix the orientation of F,
+    the factor 2, sym and the diag term at once."""
+    g = rng(41)
+    n, d = 7, 3
+    X = g.standard_normal((n, d)) @ np.diag([3.0, 2.0, 1.0]) + 0.1 * g.standard_normal((n, d))
+    S_bar, V_bar = g.standard_normal(d), g.standard_normal((d, d))
+    got = oracle.svd_backward(X[None], d, S_bar[None], V_bar[None])[0]
+    want = _fd_grad(X, d, S_bar, V_bar)
+    assert np.abs(got - want).max() < 1e-6 * max(1.0, np.abs(want).max())
+
+
+def test_svd_backward_truncated_with_vbar_in_span_and_singular_value_part():
+    """r < d with V_bar = V C: the component of V_bar outside span(V), which the formula drops
+    ("within truncated subspace"), is zero, so finite differences must agree again; with
+    V_bar = 0 the gradient is the textbook U diag(S_bar) V^T."""
+    g = rng(42)
+    n, d, r = 8, 4, 2
+    X = (g.standard_normal((n, d)) @ np.diag([4.0, 2.5, 0.7, 0.3]))
+    f = oracle.svd_factorize(X[None], r, want_u=True)
+    V = f["V"][0]
+    S_bar = g.standard_normal(r)
+    V_bar = V @ g.standard_normal((r, r))
+    got = oracle.svd_backward(X[None], r, S_bar[None], V_bar[None])[0]
+    want = _fd_grad(X, r, S_bar, V_bar)
+    assert np.abs(got - want).max() < 1e-6 * max(1.0, np.abs(want).max())
+    only_s = oracle.svd_backward(X[None], r, S_bar[None], np.zeros((1, d, r)))[0]
+    assert np.allclose(only_s, f["U"][0] @ np.diag(S_bar) @ V.T, atol=1e-12)
+    # masked rows get no gradient and do not change the rest
+    Xp = np.concatenate([X, 5.0 * np.ones((3, d))])[None]
+    gm = oracle.svd_backward(Xp, r, S_bar[None], V_bar[None], lengths=np.array([n], dtype=np.int32))[0]
+    assert np.all(gm[n:] == 0) and np.allclose(gm[:n], got, atol=1e-12)
