@@ -133,6 +133,8 @@ def main() -> int:
     ap.add_argument("--alg1", action="store_true",
                     help="also time the factorization by Algorithm 1 run as printed (passes over X) "
                          "with 0 and 1 power iterations, next to the Gram route")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time the gradient through the factorization (dL/dX from dL/dS, dL/dV)")
     ap.add_argument("--sweep", action="store_true",
                     help="also sweep the history length N at fixed M, d, r (the protocol of the paper's "
                          "forward-latency figure): softmax, linear and SVD attention on the GPU, and the "
@@ -329,6 +331,26 @@ def main() -> int:
                 "max_projector_diff_vs_gram_route": float(pv.abs().amax().item())}
         alg1["gram_route_ms_per_factorize"] = solo["gram"] + solo["eig"] + solo["project"]
         out["alg1_as_printed"] = alg1
+    if args.backward:
+        # dL/dX = P S^-1 K V^T: reads P (r floats a row), writes dX (d floats a row); the r x r and
+        # r x d work per user is negligible next to it, so the pair of kernels is HBM-bound.
+        db = sets[0]
+        db.factorize()
+        s_bar, v_bar = (torch.from_numpy(a).cuda() for a in synth.make_cotangents(w.B, w.d, w.r))
+        dX = db.backward(s_bar, v_bar, 0.0)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(args.steps):
+            db.backward(s_bar, v_bar, 0.0, dX)
+        ev1.record()
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1) / args.steps
+        nbytes = w.B * w.N * (w.r + w.d) * 4.0
+        out["svd_backward"] = {"ms": ms, "algorithmic_bytes": nbytes,
+                               "achieved_GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak":
+                               nbytes / (ms * 1e-3) / 1e9 / PEAKS["hbm_GBps"]}
+        del dX
     if args.sweep:
         out["sweep"] = latency_sweep(w, args.steps)
     if not args.no_cpu_baseline:

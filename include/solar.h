@@ -151,6 +151,24 @@ solar_status solar_apply_weights(const void* In, const float* W, int rows, int d
                                  solar_dtype t_out, void* Out, void* stream);
 
 /*
+ * Gradient through the truncated SVD with respect to X ("Backward Pass Through SVD", the form
+ * with U-bar = 0, U being eliminated from the forward pass):
+ *   dX_b = U_b [diag(S_bar_b) + 2 S_b sym(F_b o (V_b^T V_bar_b))] V_b^T,  U_b = P_b S_b^-1,
+ * sym(A) = (A + A^T)/2, F_ij = 1/(s_j^2 - s_i^2) for i != j (the orientation confirmed by finite
+ * differences; the printed F is its transpose), F_ij = 0 on the diagonal and wherever
+ * |s_i^2 - s_j^2| <= gap_rel * s_1^2 (the paper states no guard; pass 0 for none).  Only the part
+ * of V_bar inside span(V) contributes ("within truncated subspace").
+ *   S, V, P        from solar_svd_factorize (P is required)
+ *   S_bar  in  [B,r]      dL/dS          V_bar  in  [B,d,r]   dL/dV
+ *   dX     out [B,N,d] float; rows >= lengths[b] are zero
+ * Supported: d in {64, 128, 256}, r in {16, 32, 48, 64}.  Workspace: B*r*d floats
+ * (solar_workspace_bytes(...) is enough), 256-byte aligned.
+ */
+solar_status solar_svd_backward(const float* S, const float* V, const float* P, const float* S_bar,
+                                const float* V_bar, int B, int N, int d, int r, float gap_rel,
+                                float* dX, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * First phase of the factorization on its own, exported so that it can be checked
  * and profiled in isolation: G_b = X_b^T X_b over the valid rows, the contraction
  * over the sequence axis that Algorithm 1's power iteration applies to Omega.

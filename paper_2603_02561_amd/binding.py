@@ -52,6 +52,8 @@ _lib.solar_linear_attention.argtypes = [_vp, _vp, _vp, _ci, _ci, _ci, _ci, _cf, 
 _lib.solar_linear_attention.restype = _ci
 _lib.solar_apply_weights.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp]
 _lib.solar_apply_weights.restype = _ci
+_lib.solar_svd_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _cf, _vp, _vp, _sz, _vp]
+_lib.solar_svd_backward.restype = _ci
 _lib.solar_phase_timing_begin.argtypes = []
 _lib.solar_phase_timing_begin.restype = None
 _lib.solar_phase_timing_end.argtypes = [ctypes.POINTER(ctypes.c_float)]
@@ -171,6 +173,19 @@ def solar_dense_attention_ref(Q, X, lengths, scale: float, O, workspace=None,
     return rc
 
 
+def solar_svd_backward(S, V, P, S_bar, V_bar, gap_rel: float, dX, workspace,
+                       raise_on_error: bool = True) -> int:
+    _check(S, V, P, S_bar, V_bar, dX, workspace)
+    B, N, r = P.shape
+    d = V.shape[1]
+    rc = _lib.solar_svd_backward(_ptr(S), _ptr(V), _ptr(P), _ptr(S_bar), _ptr(V_bar), B, N, d, r,
+                                 float(gap_rel), _ptr(dX), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream())
+    if rc != SOLAR_OK and raise_on_error:
+        raise SolarError(rc)
+    return rc
+
+
 def solar_linear_attention(Q, X, lengths, scale: float, O, workspace, raise_on_error: bool = True) -> int:
     _check(Q, X, lengths, O, workspace)
     B, M, d = Q.shape
@@ -238,6 +253,14 @@ class DeviceBatch:
     def attention(self, scale: float, mode: int = SOLAR_ATTN_SEQ_SOFTMAX, O=None):
         return solar_svd_attention(self.Q, self.S, self.V, self.P, self.lengths, self.N, scale,
                                    mode, self.O if O is None else O, self.workspace)
+
+    def backward(self, S_bar, V_bar, gap_rel: float = 0.0, dX=None):
+        """Gradient through the factorization held in S, V, P; S_bar [B,r] and V_bar [B,d,r] are
+        float device tensors.  Returns dX [B,N,d] float."""
+        if dX is None:
+            dX = torch.empty((self.B, self.N, self.d), dtype=torch.float32, device=self.X.device)
+        solar_svd_backward(self.S, self.V, self.P, S_bar, V_bar, gap_rel, dX, self.workspace)
+        return dX
 
     def linear(self, scale: float, O=None):
         return solar_linear_attention(self.Q, self.X, self.lengths, scale, self.O if O is None else O,

@@ -219,6 +219,20 @@ solar_status solar_apply_weights(const void* In, const float* W, int rows, int d
     return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
 }
 
+solar_status solar_svd_backward(const float* S, const float* V, const float* P, const float* S_bar,
+                                const float* V_bar, int B, int N, int d, int r, float gap_rel, float* dX,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    if (!S || !V || !P || !S_bar || !V_bar || !dX || B <= 0 || N <= 0 || d <= 0 || r <= 0 || !(gap_rel >= 0.f))
+        return SOLAR_ERR_INVALID_ARG;
+    if (r > d) return SOLAR_ERR_INVALID_ARG;
+    if (!svd_backward_supported(d, r)) return SOLAR_ERR_UNSUPPORTED;
+    const size_t need = sizeof(float) * (size_t)B * r * d;
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return SOLAR_ERR_WORKSPACE;
+    hipError_t e = launch_svd_backward(S, V, P, S_bar, V_bar, B, N, d, r, gap_rel,
+                                       static_cast<float*>(workspace), dX, (hipStream_t)stream);
+    return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
+}
+
 solar_status solar_svd_attention(const void* Q, const float* S, const float* V, const float* P,
                                  const int32_t* lengths, int B, int N, int d, int r, int M,
                                  float scale, solar_attn_mode mode, solar_dtype t, float* O,

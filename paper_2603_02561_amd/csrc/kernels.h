@@ -66,6 +66,12 @@ hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* 
 hipError_t launch_rowgemm(const void* In, const float* W, size_t w_stride, int B, int rows, int d, float scale,
                           bool in_bf16, bool out_bf16, void* Out, hipStream_t stream);
 
+// backward.hip
+bool svd_backward_supported(int d, int r);
+hipError_t launch_svd_backward(const float* S, const float* V, const float* P, const float* S_bar,
+                               const float* V_bar, int B, int N, int d, int r, float gap_rel, float* Mt,
+                               float* dX, hipStream_t stream);
+
 // dense_ref.hip
 hipError_t launch_dense_ref(const void* Q, const void* X, const int32_t* lengths, int B, int N,
                             int d, int M, float scale, bool bf16, float* O, hipStream_t stream);

@@ -173,3 +173,15 @@ def make_omega(B: int, d: int, r: int, seed: int = SEED0 + 77) -> np.ndarray:
     for b in range(B):
         out[b] = np.random.default_rng(seed + b).standard_normal((d, r)).astype(np.float32)
     return out
+
+
+def make_cotangents(B: int, d: int, r: int, seed: int = SEED0 + 99):
+    """Upstream gradients for the backward pass through the factorization: S_bar [B, r] and
+    V_bar [B, d, r], float32, standard normal, one independent stream per user."""
+    S_bar = np.empty((B, r), dtype=np.float32)
+    V_bar = np.empty((B, d, r), dtype=np.float32)
+    for b in range(B):
+        g = np.random.default_rng(seed + b)
+        S_bar[b] = g.standard_normal(r).astype(np.float32)
+        V_bar[b] = g.standard_normal((d, r)).astype(np.float32)
+    return S_bar, V_bar

@@ -1,0 +1,127 @@
+"""GPU parity of the gradient through the truncated SVD ("Backward Pass Through SVD", U-bar = 0
+form) against the oracle.
+
+The operation divides by s_j^2 - s_i^2, so a relative perturbation eps of the factors moves the
+result by about eps * kappa, kappa = max_ij s_1^2 / |s_i^2 - s_j^2| (2e2 to 5e3 in these cases,
+printed per case).  Two kinds of test, both held to 1e-4 of the largest entry of the oracle's
+gradient per user (the bar for float arithmetic):
+  * the backward kernels alone, fed the oracle's own S, V, P rounded to float;
+  * factorization and backward both on the GPU.
+"""
+import numpy as np
+import pytest
+
+from paper_2603_02561_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the GPU")
+    from paper_2603_02561_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def oracle():
+    from oracle import oracle as o
+    return o
+
+
+CASES = [
+    # name, workload, gap_rel
+    ("f32_d64_r16", synth.make_workload("t", 2, 333, 64, 16, 8, synth.F32, "spectrum", 0.5, 0.0, seed=301), 0.0),
+    ("f32_d128_r32_varlen", synth.make_workload("t", 3, 700, 128, 32, 8, synth.F32, "spectrum", 0.5, 0.01,
+                                                var_len=(250, 700), seed=302), 0.0),
+    ("bf16_d128_r16", synth.make_workload("t", 2, 1000, 128, 16, 8, synth.BF16, "spectrum", 0.7, 0.01, seed=303), 0.0),
+    ("f32_d256_r48_guard", synth.make_workload("t", 2, 300, 256, 48, 8, synth.F32, "spectrum", 0.5, 0.0, seed=304),
+     1e-3),
+    ("f32_d64_r64_fullrank", synth.make_workload("t", 1, 257, 64, 64, 8, synth.F32, "spectrum", 0.5, 0.02, seed=305),
+     0.0),
+]
+
+
+def kappa(S, gap_rel):
+    s2 = S.astype(np.float64) ** 2
+    diff = np.abs(s2[:, None] - s2[None, :])
+    np.fill_diagonal(diff, np.inf)
+    diff[diff <= gap_rel * s2[0]] = np.inf
+    return s2[0] / diff.min()
+
+
+def rel_err(got, want):
+    return max(np.abs(got[b] - want[b]).max() / np.abs(want[b]).max() for b in range(want.shape[0]))
+
+
+@pytest.mark.parametrize("name,w,gap_rel", CASES, ids=[c[0] for c in CASES])
+def test_backward_kernels_on_oracle_factors(lib, oracle, name, w, gap_rel):
+    import torch
+    print(f"[case] svd backward on oracle factors {name}", flush=True)
+    S_bar, V_bar = synth.make_cotangents(w.B, w.d, w.r)
+    f = oracle.svd_factorize(w.X, w.r, w.lengths, want_u=True)
+    want = oracle.svd_backward(w.X, w.r, S_bar, V_bar, w.lengths, gap_rel)
+    db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, w.dtype == synth.BF16)
+    P = np.zeros((w.B, w.N, w.r))
+    for b in range(w.B):
+        n = int(w.lengths[b])
+        P[b, :n] = f["U"][b][:n] * f["S"][b]
+    db.S.copy_(torch.from_numpy(f["S"].astype(np.float32)))
+    db.V.copy_(torch.from_numpy(f["V"].astype(np.float32)))
+    db.P.copy_(torch.from_numpy(P.astype(np.float32)))
+    dX = db.backward(torch.from_numpy(S_bar).cuda(), torch.from_numpy(V_bar).cuda(), gap_rel)
+    torch.cuda.synchronize()
+    got = dX.cpu().numpy().astype(np.float64)
+    k = max(kappa(f["S"][b], gap_rel) for b in range(w.B))
+    tol = 1e-4
+    err = rel_err(got, want)
+    print(f"  kappa {k:.3e} err {err:.3e} tol {tol:.3e}", flush=True)
+    assert err < tol
+    for b in range(w.B):
+        assert np.all(got[b, int(w.lengths[b]):] == 0)
+
+
+@pytest.mark.parametrize("name,w,gap_rel", CASES[:3], ids=[c[0] for c in CASES[:3]])
+def test_factorize_then_backward(lib, oracle, name, w, gap_rel):
+    import torch
+    print(f"[case] svd factorize + backward {name}", flush=True)
+    S_bar, V_bar = synth.make_cotangents(w.B, w.d, w.r)
+    want = oracle.svd_backward(w.X, w.r, S_bar, V_bar, w.lengths, gap_rel)
+    db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, w.dtype == synth.BF16)
+    db.factorize()
+    dX = db.backward(torch.from_numpy(S_bar).cuda(), torch.from_numpy(V_bar).cuda(), gap_rel)
+    torch.cuda.synchronize()
+    assert int(db.info.abs().max()) == 0
+    got = dX.cpu().numpy().astype(np.float64)
+    S = db.S.cpu().numpy()
+    k = max(kappa(S[b], gap_rel) for b in range(w.B))
+    tol = 1e-4
+    err = rel_err(got, want)
+    print(f"  kappa {k:.3e} err {err:.3e} tol {tol:.3e}", flush=True)
+    assert err < tol
+
+
+def test_backward_rejects_bad_arguments(lib):
+    import torch
+    w = synth.make_workload("t", 1, 64, 64, 16, 8, synth.F32, "spectrum", 0.5, 0.0, seed=306)
+    db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, False)
+    db.factorize()
+    S_bar = torch.zeros((1, 16), device="cuda")
+    V_bar = torch.zeros((1, 64, 16), device="cuda")
+    dX = torch.empty((1, 64, 64), device="cuda")
+    small = torch.empty((256,), dtype=torch.uint8, device="cuda")
+    assert lib.solar_svd_backward(db.S, db.V, db.P, S_bar, V_bar, 0.0, dX, small, raise_on_error=False) \
+        == 3
+    assert lib.solar_svd_backward(db.S, db.V, db.P, S_bar, V_bar, -1.0, dX, db.workspace, raise_on_error=False) \
+        == 1
+    # r = 8 is outside the supported set
+    w8 = synth.make_workload("t", 1, 64, 64, 8, 8, synth.F32, "gauss_lowrank", seed=307)
+    d8 = lib.DeviceBatch(w8.X, w8.Q, w8.lengths, 8, False)
+    d8.factorize()
+    rc = lib.solar_svd_backward(d8.S, d8.V, d8.P, torch.zeros((1, 8), device="cuda"),
+                                torch.zeros((1, 64, 8), device="cuda"), 0.0, dX, d8.workspace,
+                                raise_on_error=False)
+    assert rc == 2
+    torch.cuda.synchronize()
