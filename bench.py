@@ -236,7 +236,7 @@ def main() -> int:
     info_bad = int((sets[0].info != 0).sum().item())
 
     # Algorithmic work per launch (whole batch): what the method must move or compute, not
-    # what the kernels happen to do ("Kernels and rooflines").
+    # what the kernels happen to do.
     lens = w.lengths.astype(np.float64)
     e = 2 if bf16 else 4
     work = {
@@ -263,6 +263,15 @@ def main() -> int:
             kernels.setdefault(name, {"kernel": kernel_names[name], "bound": bound, "unit": unit,
                                       "peak": peak, "algorithmic": amount})[label] = {
                 "ms": ms, "achieved": achieved, "frac": achieved / peak}
+    # second bound of the attention kernel: one exponential per (candidate, key) pair; v_exp_f32
+    # issues at half the plain vector rate (8 lanes per clock per SIMD, measured 8.35 cycles per
+    # wave instruction): 256 CUs x 4 SIMDs x 8 x 2.4 GHz
+    n_exp = float(np.sum(w.M * lens))
+    exp_peak = 256 * 4 * 8 * 2.4e9 / 1e12
+    kernels["attention"]["exp_bound"] = {
+        "exponentials": n_exp, "peak_Texp_per_s": exp_peak,
+        "alone": {"achieved": n_exp / (solo["attention"] * 1e-3) / 1e12,
+                  "frac": n_exp / (solo["attention"] * 1e-3) / 1e12 / exp_peak}}
     kernels["eig"] = {"kernel": kernel_names["eig"], "bound": "latency (serial Jacobi rounds, one "
                       "workgroup per user; no roofline)", "pipelined": {"ms": eig_ms},
                       "alone": {"ms": solo["eig"]}}
