@@ -12,8 +12,12 @@
 //   * row sums of the rounded weights by one more MFMA per 16 rows against a tile of ones:
 //     it costs the issue port a fraction of what a chain of dependent vector adds or packed
 //     dot products costs (their result latency is exposed), and the matrix pipe has room;
-//   * the softmax reference moves lazily: a block's scores are only compared against it
-//     (a maximum over the lane's 16 scores, taken while the block before is exponentiated).
+//   * the softmax reference is not maintained at all on the first, optimistic pass over the
+//     sequence (it stays a few log2 units above the first block's maximum; a weight that
+//     leaves the fp16 range turns the row sum infinite), and only a workgroup that saw that
+//     happen repeats the sequence with a guarded pass whose reference moves lazily: a
+//     block's scores are compared against it (a maximum over the lane's 16 scores, taken
+//     while the block before is exponentiated).
 //
 // P and Qt are rounded to fp16 once (11-bit significands; P is first scaled by 1/S[0] when
 // S[0] lies outside [1, 2^13]); the scores carry about 2^-11 relative error, inside the 2e-2
@@ -36,6 +40,7 @@
 // converted) and, inside a tile, in blocks of 32 rows through a software pipeline: while the
 // exponentials of block j run, the matrix unit computes the scores of block j+1 and adds
 // block j-1 to Z.
+#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -61,6 +66,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 #define SOLAR_X32_KSHIFT 8.f
 #endif
 constexpr float kShift = SOLAR_X32_KSHIFT;
+// optimistic pass: the reference stays kHead log2 units above the largest score of the first
+// block, so weights stay inside the fp16 range while no score lies more than 16 + kHead above it
+constexpr float kHead = 4.f;
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v2h __attribute__((ext_vector_type(2)));
@@ -100,10 +108,11 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const void* __restrict__ Qv, const float* __restrict__ S, const float* __restrict__ V,
     const float* __restrict__ P, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
-    float scale, float* __restrict__ O) {
+    float scale, int guarded_only, float* __restrict__ O) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                                              // [D][LDV]
     uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);   // [3][kBuf]
+    int* redo = reinterpret_cast<int*>(tiles + 3 * kBuf);          // set when a wave's optimistic pass overflowed
     // Workgroups are dealt to the 8 XCDs round-robin by linear id.  All M-tiles of a user
     // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
     const int mtiles = ceil_div(M, kWaves * kQW);
@@ -131,6 +140,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     }
     // zero the tile buffers once: padded rank columns stay zero for ever
     for (int e = tid; e < 3 * kBuf / 2; e += kThreads) reinterpret_cast<uint32_t*>(tiles)[e] = 0u;
+    if (tid == 0) *redo = 0;
     __syncthreads();
 
     // ---- prologue: Qt^T = V^T Q^T in float (32x32x2 MFMA; the contraction slot of lane half
@@ -222,15 +232,19 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     v16f cinit;         // -mref in every register: start value of the score accumulators
     v16f lacc;          // row sum of the weights of query n32 in every register
     float mref = 0.f;
-    float smax = 0.f;   // largest score of the lane in the block that is exponentiated next
+    float smax = 0.f;   // guarded pass: largest score of the lane in the block that is exponentiated next
     const v4u ones = v4u{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};   // eight fp16 ones
+    auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int t = 0; t < 16; ++t) { z[t] = 0.f; cinit[t] = 0.f; lacc[t] = 0.f; }
+        for (int t = 0; t < 16; ++t) { z[t] = 0.f; cinit[t] = 0.f; lacc[t] = 0.f; }
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        wp[0][c] = wp[1][c] = v4u{0u, 0u, 0u, 0u};
-        zA[0][c] = zA[1][c] = v4u{0u, 0u, 0u, 0u};
-    }
+        for (int c = 0; c < 2; ++c) {
+            wp[0][c] = wp[1][c] = v4u{0u, 0u, 0u, 0u};
+            zA[0][c] = zA[1][c] = v4u{0u, 0u, 0u, 0u};
+        }
+        mref = 0.f; smax = 0.f;
+        ld_off = (uint32_t)(2 * ld_np) * row_bytes + ld_col;
+    };
 
     // Online softmax with a lazily updated reference: weights are exp2(s - mref) and may exceed
     // one.  The scores of a block are compared with the reference before they are
@@ -238,13 +252,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // block) is the block maximum formed per query, mref moved there for the queries that need
     // it, and everything that is relative to the old reference rescaled: Z, the row sums and
     // the packed weights of the block before, whose Z product is still to be issued.
-    auto move_reference = [&](int cur, bool first) __attribute__((always_inline)) {
-        float v = -INFINITY;
-#pragma unroll
-        for (int t = 0; t < 16; ++t) v = fmaxf(v, s[cur][t]);
-        v = wave_xor_max(v, 32);   // block maximum of the query, relative to mref
-        const float shift = (first || v > kShift) ? v : 0.f;
-        const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-shift);
+    // everything that is relative to the reference moves with it by shift (log2 units)
+    auto apply_shift = [&](int cur, float shift, float alpha) __attribute__((always_inline)) {
         mref += shift;
         const _Float16 ah = (_Float16)alpha;
 #pragma unroll
@@ -257,6 +266,14 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 #pragma unroll
         for (int c = 0; c < 2; ++c)
             wp[cur ^ 1][c] = __builtin_bit_cast(v4u, __builtin_bit_cast(v8h, wp[cur ^ 1][c]) * ah);
+    };
+    auto move_reference = [&](int cur, bool first, float head) __attribute__((always_inline)) {
+        float v = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) v = fmaxf(v, s[cur][t]);
+        v = wave_xor_max(v, 32);   // block maximum of the query, relative to mref
+        const float shift = first ? v + head : (v > kShift ? v : 0.f);
+        apply_shift(cur, shift, first ? 0.f : __builtin_amdgcn_exp2f(-shift));
     };
     // rows of the block past the valid length get weight zero
     auto mask_block = [&](int cur, int j) __attribute__((always_inline)) {
@@ -278,18 +295,25 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // Every MFMA is issued at raised wave priority, so that the matrix unit is fed ahead of the
     // other wave's vector work.
 #define SOLAR_FENCE __builtin_amdgcn_sched_barrier(0)
-    auto slot = [&](int j, auto cur_tag, const uint16_t* sa_next, const uint16_t* za_this)
+    auto slot = [&](int j, auto cur_tag, auto guard_tag, const uint16_t* sa_next, const uint16_t* za_this)
                     __attribute__((always_inline)) {
         constexpr int cur = decltype(cur_tag)::value, nxt = cur ^ 1;
+        constexpr bool guarded = decltype(guard_tag)::value;
         mask_block(cur, j);
-        if (__builtin_expect(__any(smax > kShift), 0)) move_reference(cur, false);   // uniform over the wave, rare
+        if constexpr (guarded) {
+            if (__builtin_expect(__any(smax > kShift), 0)) move_reference(cur, false, 0.f);   // uniform over the wave, rare
+        }
         float w[16];
         auto E = [&](int t) __attribute__((always_inline)) { w[t] = __builtin_amdgcn_exp2f(s[cur][t]); };
         // pack weights 2*e, 2*e+1 of the block (e = 0..7)
-        auto C = [&](int e) __attribute__((always_inline)) { wp[cur][e / 4][e % 4] = pack_f16_rtz(w[2 * e], w[2 * e + 1]); };
+        // (optimistic pass: to nearest, so that a weight beyond the fp16 range becomes infinite
+        // and shows in the row sum)
+        auto C = [&](int e) __attribute__((always_inline)) {
+            wp[cur][e / 4][e % 4] = guarded ? pack_f16_rtz(w[2 * e], w[2 * e + 1]) : pack_f16(w[2 * e], w[2 * e + 1]);
+        };
         // running maximum of the scores of block j+1 (registers 4*i .. 4*i+3)
         auto X = [&](int i) __attribute__((always_inline)) {
-            smax = fmaxf(fmaxf(i == 0 ? s[nxt][0] : smax, s[nxt][4 * i + (i == 0 ? 1 : 0)]),
+            if constexpr (guarded) smax = fmaxf(fmaxf(i == 0 ? s[nxt][0] : smax, s[nxt][4 * i + (i == 0 ? 1 : 0)]),
                          fmaxf(s[nxt][4 * i + (i == 0 ? 2 : 1)], fmaxf(s[nxt][4 * i + (i == 0 ? 3 : 2)], s[nxt][4 * i + 3])));
         };
         SOLAR_FENCE;
@@ -359,8 +383,20 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     };
 
     // ---- the sequence loop ---------------------------------------------------------------------
+    // Two versions of one pass over the sequence.  The optimistic one keeps the reference where
+    // the first block put it (kHead above that block's largest score) and spends nothing on the
+    // scores before they are exponentiated.  It is exact as long as every weight fits fp16,
+    // i.e. no score lies 16 + kHead log2 units above the first block's maximum; a weight
+    // beyond that rounds to infinity, which the row sum keeps.  If that happened to any query
+    // of the workgroup, the guarded version (block maxima before every exponentiation, lazily
+    // moving reference) runs the sequence again from the start.
     const int ntiles = ceil_div(len, kNT);
     const int nblocks = ceil_div(len, 32);
+    using tag0 = std::integral_constant<int, 0>;
+    using tag1 = std::integral_constant<int, 1>;
+    auto pass = [&](auto guard_tag) __attribute__((always_inline)) {
+    constexpr bool guarded = decltype(guard_tag)::value;
+    reset_state();
     if (ntiles > 0) { fetch(0); commit(tiles, 0); }
     if (ntiles > 1) { fetch(1); commit(tiles + kBuf, 1); }
     __syncthreads();
@@ -376,10 +412,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 #pragma unroll
         for (int t = 0; t < 16; ++t) s[1][t] = 0.f;
         mask_block(0, 0);
-        move_reference(0, true);
+        move_reference(0, true, guarded ? 0.f : kHead);
     }
-    using tag0 = std::integral_constant<int, 0>;
-    using tag1 = std::integral_constant<int, 1>;
     // byte-free rotation of the three tile buffers: element offsets of the tile being
     // multiplied, the next one and the one being converted
     int o_cur = 0, o_nxt = kBuf, o_wr = 2 * kBuf;
@@ -390,15 +424,14 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         const uint16_t* sa_nxt = tiles + o_nxt + sa_off;
         const uint16_t* za_cur = tiles + o_cur + za_off;
         const int j0 = tile * kNB;
-        slot(j0, tag0{}, sa_cur + 2 * 32 * LDR, za_cur);
-        if (__builtin_expect(j0 + 1 < nblocks, 1)) slot(j0 + 1, tag1{}, sa_cur + 3 * 32 * LDR, za_cur + 32 * LDR);
+        slot(j0, tag0{}, guard_tag, sa_cur + 2 * 32 * LDR, za_cur);
+        if (__builtin_expect(j0 + 1 < nblocks, 1)) slot(j0 + 1, tag1{}, guard_tag, sa_cur + 3 * 32 * LDR, za_cur + 32 * LDR);
         if (__builtin_expect(ahead, 1)) commit(tiles + o_wr, tile + 2);
-        if (__builtin_expect(j0 + 2 < nblocks, 1)) slot(j0 + 2, tag0{}, sa_nxt, za_cur + 2 * 32 * LDR);
-        if (__builtin_expect(j0 + 3 < nblocks, 1)) slot(j0 + 3, tag1{}, sa_nxt + 32 * LDR, za_cur + 3 * 32 * LDR);
+        if (__builtin_expect(j0 + 2 < nblocks, 1)) slot(j0 + 2, tag0{}, guard_tag, sa_nxt, za_cur + 2 * 32 * LDR);
+        if (__builtin_expect(j0 + 3 < nblocks, 1)) slot(j0 + 3, tag1{}, guard_tag, sa_nxt + 32 * LDR, za_cur + 3 * 32 * LDR);
         __syncthreads();
         const int o = o_cur; o_cur = o_nxt; o_nxt = o_wr; o_wr = o;
     }
-#undef SOLAR_FENCE
     // Z of the last block trails the loop
     if (nblocks > 0) {
         if ((nblocks - 1) & 1) {
@@ -409,6 +442,19 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             z = mma32(zA[0][1], wp[0][1], z);
         }
     }
+    };
+    if (__builtin_expect(!guarded_only, 1)) {
+        pass(std::false_type{});
+        if (!(lacc[0] < 3.0e38f)) *redo = 1;   // some weight left the fp16 range (or the input is not finite)
+    } else if (tid == 0) {
+        *redo = 1;
+    }
+    __syncthreads();
+    if (__builtin_expect(*redo != 0, 0)) {   // uniform over the workgroup
+        __syncthreads();
+        pass(std::true_type{});
+    }
+#undef SOLAR_FENCE
 
     // ---- epilogue in float: O^T = V (Z / l)^T with the 32x32x2 MFMA: step t contracts the
     // ranks of register t (one per lane half) -----------------------------------------------------
@@ -439,13 +485,15 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 template <int D>
 hipError_t launch_d(const void* Q, const float* S, const float* V, const float* P, const int32_t* lengths,
                     int B, int N, int r, int M, float scale, float* O, hipStream_t stream) {
-    const size_t lds = sizeof(float) * (size_t)D * LDV + sizeof(uint16_t) * 3 * (size_t)kBuf;
+    // debugging aid: skip the optimistic pass
+    const int guarded_only = std::getenv("SOLAR_X32_GUARDED") != nullptr;
+    const size_t lds = sizeof(float) * (size_t)D * LDV + sizeof(uint16_t) * 3 * (size_t)kBuf + 16;
     dim3 grid(ceil_div(M, kWaves * kQW) * 8 * ceil_div(B, 8)), block(kThreads);
     auto kern = attention_seq_x32_kernel<D>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, P, lengths, B, N, r, M, scale, O);
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, P, lengths, B, N, r, M, scale, guarded_only, O);
     return hipGetLastError();
 }
 
