@@ -459,8 +459,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_bf16_kernel(
         // scheduler otherwise bunches the matrix and the vector work of a stage.  A stage is
         // kNB slots; a slot issues its share of the stage's matrix units, the four
         // exponentials of one 16-row block and the two packs of the block before (a pack right
-        // behind its exponentials would wait for them; issued a slot later it falls into the
-        // shadow of the transcendental unit).
+        // behind its exponentials would wait for them; issued a slot later it does not).
         constexpr int kNB = kNT / 16;
         constexpr int kUZ = (kNT / 32) * RB;   // Z units of a query block
         auto z_unit = [&](int qb, int u) __attribute__((always_inline)) {

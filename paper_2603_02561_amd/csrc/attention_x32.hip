@@ -3,9 +3,9 @@
 // on the 32x32x16 fp16 matrix instruction of gfx950.
 //
 // The kernel is bound by the issue port of the vector ALU, which the matrix instructions
-// share: every MFMA holds the port for about eight cycles whatever its shape, an
-// exponential for about eight (half rate), and the ordinary instructions that follow an
-// exponential (packs, dot products) fall into the second half of its slot for free.  Hence
+// share.  Measured per wave instruction: an MFMA holds the port for about 8 cycles whatever
+// its shape, an exponential (f32 or f16) for 8.5, a float-pair-to-fp16 pack for 7.4, a plain
+// operation for 5.  Hence
 //   * 32x32x16 products: one instruction covers 1024 scores where the 16x16x32 shape covers
 //     256, so a block of 32 rows of P against 32 queries costs two MFMAs for the scores and
 //     two for Z^T += P^T W^T;
@@ -286,11 +286,10 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 
     // One slot of the pipeline, block j of parity cur = j % 2: E(j) on the vector ALU next to
     // S(j+1), Z(j-1) and the row sums of block j on the matrix unit, the maximum of the scores
-    // of block j+1, and the LDS reads for S(j+2) and Z(j).  The order
-    // of issue is written out and fenced pair by pair: an exponential occupies the
-    // transcendental unit for two issue slots, and the instruction placed right behind it
-    // (a pack or a row sum of the group of exponentials before, an LDS read) issues in its
-    // shadow; bunched behind four exponentials those instructions would each cost a slot.
+    // of block j+1 (guarded pass), and the LDS reads for S(j+2) and Z(j).  The order of issue is
+    // written out and fenced pair by pair: a pack waits for its two exponentials, so it sits
+    // behind the exponentials of the group after, and the matrix instructions are spread
+    // between the groups so that each finds the matrix pipe free.
     // sa_next and za_this point at the score operands of block j+2 and the Z operands of block j.
     // Every MFMA is issued at raised wave priority, so that the matrix unit is fed ahead of the
     // other wave's vector work.
