@@ -60,6 +60,7 @@ EigParams eig_params_from_env() {
     EigParams p = eig_default_params();
     // Debug overrides for tuning the eigen-iteration without a rebuild.
     if (const char* s = std::getenv("SOLAR_EIG_TOL")) p.tol_res = (float)std::atof(s);
+    if (const char* s = std::getenv("SOLAR_EIG_ORTH")) p.tol_orth = (float)std::atof(s);
     if (const char* s = std::getenv("SOLAR_EIG_SWEEPS")) p.sweeps = std::atoi(s);
     if (const char* s = std::getenv("SOLAR_EIG_MAXIT")) p.max_iter = std::atoi(s);
     if (const char* s = std::getenv("SOLAR_EIG_DEBUG")) p.debug_counts = std::atoi(s);

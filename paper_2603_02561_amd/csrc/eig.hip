@@ -40,10 +40,14 @@ constexpr int kEigWaves = kEigThreads / 64;
 // A column of the iterate whose norm falls below this fraction of the largest column norm
 // is rounding noise of the float Gram matrix (about sqrt(d) * 2^-24 relative) and is dropped.
 constexpr float kDeadRel = 1.0e-5f;
-// Rotations are skipped below this |cos|; a sweep that meets no |cos| above kSweepDone
-// leaves every |cos| below about L * kSweepDone^2 (quadratic convergence) and ends the phase.
+// Rotations are skipped below kSkipCos.  The Jacobi phase converges quadratically: a sweep whose
+// largest |cos| was c leaves about c^2 behind (L * c^2 at worst), so the phase ends after the
+// first sweep that met no |cos| above kSweepDone = 1e-3, with a few 1e-6 left; the residual
+// check of the following power step is what accepts the result.  (2e-4 costs one more sweep
+// in a third of the cases; 3e-3 leaves V^T V up to 4e-5 off the identity at 72 columns; 3e-2
+// makes the check fail and the iteration longer.)
 constexpr float kSkipCos = 1.0e-7f;
-constexpr float kSweepDone = 2.0e-4f;
+constexpr float kSweepDone = 1.0e-3f;
 
 __host__ __device__ constexpr int pow2floor_c(int x) {
     int p = 1;
@@ -355,7 +359,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
         for (int sw = 0; sw < prm.sweeps; ++sw) {
             const float mine = jacobi_sweep<D, L>(Zc, dead2);
             ++total_sweeps;
-            const bool any = __syncthreads_or(mine > kSweepDone);
+            const bool any = __syncthreads_or(mine > prm.tol_orth);
             if (!any) { orth_ok = true; break; }
         }
         cyc_jac += clock64() - t0;
@@ -590,7 +594,7 @@ hipError_t launch_eig_d(const float* G, const int32_t* lengths, int B, int N, in
 EigParams eig_default_params() {
     EigParams p;
     p.tol_res = 5.0e-6f;
-    p.tol_orth = 2.0e-6f;
+    p.tol_orth = kSweepDone;
     p.max_iter = 40;
     p.sweeps = 12;
     p.mgs_steps = 2;
