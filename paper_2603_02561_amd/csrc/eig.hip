@@ -92,19 +92,21 @@ __device__ __forceinline__ float team_sum(float v) {
 // Z = G Q with the float 16x16x4 MFMA, 16x16 output blocks dealt round-robin to the
 // waves.  G is symmetric, so A[i][k] = G[k][i] is read with the 16 lanes of a slot group
 // on consecutive addresses.  Q and Z are stored column by column (column j at j*LD).
-template <int D, int LP>
-__device__ __forceinline__ void gemm_gq(const float* __restrict__ Gb, const float* Qc, float* Zc) {
+// Gb has row stride GS: the copy of G in LDS (row stride D + 16, which puts the two slot
+// groups of a half wave on disjoint banks) or, when G does not fit there, G itself.
+template <int D, int LP, int GS>
+__device__ __forceinline__ void gemm_gq(const float* Gb, const float* Qc, float* Zc) {
     constexpr int LD = D + 4;
     constexpr int NRB = D / 16, NB = NRB * (LP / 16);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i16 = lane & 15, g = lane >> 4;
     for (int blk = wave; blk < NB; blk += kEigWaves) {
         const int ib = blk % NRB, cb = blk / NRB;
-        const float* ga = Gb + (size_t)g * D + 16 * ib + i16;
+        const float* ga = Gb + g * GS + 16 * ib + i16;
         const float* qb = Qc + (16 * cb + i16) * LD + g;
         v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 16
-        for (int k0 = 0; k0 < D; k0 += 4) acc = mfma16x16x4(ga[(size_t)k0 * D], qb[k0], acc);
+        for (int k0 = 0; k0 < D; k0 += 4) acc = mfma16x16x4(ga[k0 * GS], qb[k0], acc);
         *reinterpret_cast<v4f*>(&Zc[(16 * cb + i16) * LD + 16 * ib + 4 * g]) = acc;
     }
 }
@@ -119,7 +121,10 @@ struct EigCfg {
     static constexpr int TJ = min_c(min_c(SOLAR_EIG_TMAX, D / 4), pow2floor_c(kEigThreads / NPAIR));
     static constexpr int CH = D / (4 * TJ);
     static constexpr int TC = min_c(min_c(64, D), pow2floor_c(kEigThreads / L));
-    static constexpr size_t lds_floats = (size_t)2 * LP * LD + 3 * LP + 8;
+    // G is staged in LDS when it fits beside the two iterate blocks
+    static constexpr bool GLDS = D <= 128;
+    static constexpr int GS = GLDS ? D + 16 : D;
+    static constexpr size_t lds_floats = (size_t)2 * LP * LD + 3 * LP + 8 + (GLDS ? (size_t)D * GS : 0);
 };
 
 // One cyclic sweep of one-sided Jacobi over the L columns of Zc: L-1 rounds of L/2
@@ -182,65 +187,89 @@ __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
     return offmax;
 }
 
-// One pass of modified Gram-Schmidt over the L columns of Zc, then normalization into Qc:
-// a cheap orthonormal basis of span(Z) for the early power steps, where only the span
-// matters.  Step j projects column j out of every later column (one team of TM lanes per
-// later column; the team also recomputes |z_j|^2, so a step needs a single barrier).
-// Columns that collapse below dead2 (squared norm) are dropped.  The basis is orthonormal
-// to about 2^-24 * cond(Z), which is all a power step needs.
+// One pass of modified Gram-Schmidt over the L columns of Zc, normalized into Qc: a cheap
+// orthonormal basis of span(Z) for the early power steps, where only the span matters.  The
+// columns are taken in panels of kPanel: every team of TM lanes loads the panel and
+// orthogonalizes it in registers (all teams do the same arithmetic in the same order, so they
+// hold the same bits), team i writes panel column i, normalized, to Qc, and each team then
+// projects the panel, column after column, out of the later columns it owns.  The order of
+// the projections is that of column-by-column Gram-Schmidt; a panel costs one barrier where
+// that costs kPanel.  Columns that collapse below dead2 (squared norm) are dropped (zero in Qc).
+// The basis is orthonormal to about 2^-24 * cond(Z), which is all a power step needs.
+constexpr int kPanel = 4;
+
+template <int CH>
+__device__ __forceinline__ float dot_ch(const v4f* a, const v4f* b) {
+    float g = 0.f;
+#pragma unroll
+    for (int k = 0; k < CH; ++k) g += a[k].x * b[k].x + a[k].y * b[k].y + a[k].z * b[k].z + a[k].w * b[k].w;
+    return g;
+}
+
 template <int D, int L>
 __device__ __forceinline__ void mgs_orthonormalize(float* Zc, float* Qc, float dead2) {
+    static_assert(L % kPanel == 0, "the block is a whole number of panels");
     constexpr int LD = D + 4;
     constexpr int TM = min_c(16, D / 4);         // lanes per column
     constexpr int CH = D / (4 * TM);
     constexpr int NTEAM = kEigThreads / TM;
+    static_assert(NTEAM >= kPanel, "one team per panel column");
     const int tid = threadIdx.x;
     const int team = tid / TM, u = tid % TM;
 #pragma unroll 1
-    for (int j = 0; j < L - 1; ++j) {
-        const float* zj = Zc + j * LD + 4 * u;
-        v4f a[CH];
+    for (int p0 = 0; p0 < L; p0 += kPanel) {
+        v4f a[kPanel][CH];
+        float inv[kPanel], nrm[kPanel];
 #pragma unroll
-        for (int k = 0; k < CH; ++k) a[k] = *reinterpret_cast<const v4f*>(zj + 4 * TM * k);
-        float njj = 0.f;
+        for (int i = 0; i < kPanel; ++i) {
+            const float* zi = Zc + (p0 + i) * LD + 4 * u;
 #pragma unroll
-        for (int k = 0; k < CH; ++k) njj += a[k].x * a[k].x + a[k].y * a[k].y + a[k].z * a[k].z + a[k].w * a[k].w;
-        njj = team_sum<TM>(njj);
-        if (njj > dead2) {
-            const float inv = 1.f / njj;
-            for (int c = j + 1 + team; c < L; c += NTEAM) {
-                float* zc = Zc + c * LD + 4 * u;
-                v4f b[CH];
-                float g = 0.f;
+            for (int k = 0; k < CH; ++k) a[i][k] = *reinterpret_cast<const v4f*>(zi + 4 * TM * k);
+        }
 #pragma unroll
-                for (int k = 0; k < CH; ++k) {
-                    b[k] = *reinterpret_cast<const v4f*>(zc + 4 * TM * k);
-                    g += a[k].x * b[k].x + a[k].y * b[k].y + a[k].z * b[k].z + a[k].w * b[k].w;
-                }
-                g = team_sum<TM>(g) * inv;
+        for (int i = 0; i < kPanel; ++i) {
+            float g[kPanel];
 #pragma unroll
-                for (int k = 0; k < CH; ++k) *reinterpret_cast<v4f*>(zc + 4 * TM * k) = b[k] - g * a[k];
+            for (int k = i; k < kPanel; ++k) g[k] = dot_ch<CH>(a[i], a[k]);
+#pragma unroll
+            for (int k = i; k < kPanel; ++k) g[k] = team_sum<TM>(g[k]);
+            nrm[i] = g[i];
+            inv[i] = g[i] > dead2 ? 1.f / g[i] : 0.f;
+#pragma unroll
+            for (int k = i + 1; k < kPanel; ++k) {
+                const float c = g[k] * inv[i];
+#pragma unroll
+                for (int q = 0; q < CH; ++q) a[k][q] -= c * a[i][q];
             }
+        }
+        // team i owns panel column i: normalized into Qc (nobody reads Qc during the pass)
+        if (team < kPanel) {
+#pragma unroll
+            for (int i = 0; i < kPanel; ++i) {
+                if (team == i) {
+                    const float sc = nrm[i] > dead2 ? __builtin_amdgcn_rsqf(nrm[i]) : 0.f;
+                    float* qi = Qc + (p0 + i) * LD + 4 * u;
+#pragma unroll
+                    for (int k = 0; k < CH; ++k) *reinterpret_cast<v4f*>(qi + 4 * TM * k) = a[i][k] * sc;
+                }
+            }
+        }
+        for (int c = p0 + kPanel + team; c < L; c += NTEAM) {
+            float* zc = Zc + c * LD + 4 * u;
+            v4f b[CH];
+#pragma unroll
+            for (int k = 0; k < CH; ++k) b[k] = *reinterpret_cast<const v4f*>(zc + 4 * TM * k);
+#pragma unroll
+            for (int i = 0; i < kPanel; ++i) {
+                const float g = team_sum<TM>(dot_ch<CH>(a[i], b)) * inv[i];
+#pragma unroll
+                for (int k = 0; k < CH; ++k) b[k] -= g * a[i][k];
+            }
+#pragma unroll
+            for (int k = 0; k < CH; ++k) *reinterpret_cast<v4f*>(zc + 4 * TM * k) = b[k];
         }
         __syncthreads();
     }
-    // normalize (dead columns become zero)
-    for (int c = team; c < L; c += NTEAM) {
-        const float* zc = Zc + c * LD + 4 * u;
-        float* qc = Qc + c * LD + 4 * u;
-        v4f b[CH];
-        float nn = 0.f;
-#pragma unroll
-        for (int k = 0; k < CH; ++k) {
-            b[k] = *reinterpret_cast<const v4f*>(zc + 4 * TM * k);
-            nn += b[k].x * b[k].x + b[k].y * b[k].y + b[k].z * b[k].z + b[k].w * b[k].w;
-        }
-        nn = team_sum<TM>(nn);
-        const float inv = nn > dead2 ? __builtin_amdgcn_rsqf(nn) : 0.f;
-#pragma unroll
-        for (int k = 0; k < CH; ++k) *reinterpret_cast<v4f*>(qc + 4 * TM * k) = b[k] * inv;
-    }
-    __syncthreads();
 }
 
 template <int D, int L>
@@ -255,6 +284,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     float* theta = Qc + LP * LD;   // [LP]
     float* resid = theta + LP;     // [LP] residuals, also column norms
     int* rankv = reinterpret_cast<int*>(resid + LP);              // [LP]
+    float* Gs = resid + 2 * LP + 8;                               // [D][GS] when C::GLDS
     __shared__ int sh_bits;
     __shared__ int sh_bits2;
     const int tid = threadIdx.x;
@@ -271,6 +301,13 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
         }
     }
     if (tid == 0) { sh_bits = 0; sh_bits2 = 0; }
+    if constexpr (C::GLDS) {
+        for (int e = tid; e < D * D / 4; e += kEigThreads) {
+            const int i = e / (D / 4), c4 = e % (D / 4);
+            *reinterpret_cast<v4f*>(Gs + i * C::GS + 4 * c4) = *reinterpret_cast<const v4f*>(Gb + (size_t)i * D + 4 * c4);
+        }
+    }
+    const float* Gop = C::GLDS ? Gs : Gb;
     // start block Omega (columns >= L stay zero so that the padded GEMM columns are zero)
     for (int e = tid; e < LP * D; e += kEigThreads) {
         const int j = e / D, i = e % D;
@@ -292,14 +329,15 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     bool have_ritz = false;
     int cheap_left = prm.mgs_steps;
     int cycle = 0;
-    long long cyc_gemm = 0, cyc_jac = 0;
+    long long cyc_gemm = 0, cyc_jac = 0, cyc_mgs = 0, cyc_chk = 0;
     const long long wall0 = wall_clock64();
     const long long cyc0 = clock64();
     for (;; ++it) {
         long long t0 = clock64();
-        gemm_gq<D, LP>(Gb, Qc, Zc);
+        gemm_gq<D, LP, C::GS>(Gop, Qc, Zc);
         __syncthreads();
         cyc_gemm += clock64() - t0;
+        t0 = clock64();
         // column norms of Z (for the dead-column threshold), Rayleigh quotients and residuals
         if (col < L) {
             const float* q = Qc + col * LD;
@@ -342,11 +380,14 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
             if (it >= prm.max_iter) { status = it; break; }
         }
         __syncthreads();
+        cyc_chk += clock64() - t0;
         if (tid == 0) { sh_bits = 0; sh_bits2 = 0; }
         if (cheap_left > 0) {
             --cheap_left;
             have_ritz = false;
+            t0 = clock64();
             mgs_orthonormalize<D, L>(Zc, Qc, dead2);
+            cyc_mgs += clock64() - t0;
             continue;
         }
         // a failed check means slow convergence: spend more cheap steps before the next one
@@ -410,6 +451,9 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
         if (prm.debug_counts == 3) v = (int)(cyc_gemm / (it + 1));                   // cycles per GEMM
         if (prm.debug_counts == 4) v = (int)(wall_clock64() - wall0);                // 100 MHz ticks
         if (prm.debug_counts == 5) v = (int)((clock64() - cyc0) / 1000);             // kilo-cycles
+        if (prm.debug_counts == 6) v = (int)cyc_mgs;
+        if (prm.debug_counts == 7) v = (int)cyc_chk;
+        if (prm.debug_counts == 8) v = (int)cyc_jac;
         info[b] = v;
     }
 }
@@ -613,7 +657,7 @@ int eig_block_columns(int d, int r) {
 size_t eig_lds_bytes(int d, int r) {
     const int L = eig_block_columns(d, r);
     const int LP = 16 * ((L + 15) / 16);
-    return sizeof(float) * ((size_t)2 * LP * (d + 4) + 3 * LP + ((L - 1) * (L / 2) + 1) / 2 + 8);
+    return sizeof(float) * ((size_t)2 * LP * (d + 4) + 3 * LP + 8 + (d <= 128 ? (size_t)d * (d + 16) : 0));
 }
 
 hipError_t launch_eig(const float* G, const int32_t* lengths, int B, int N, int d, int r, float* S,
