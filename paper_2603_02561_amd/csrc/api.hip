@@ -117,7 +117,7 @@ solar_status solar_gram(const void* X, const int32_t* lengths, int B, int N, int
     if (!supported_shape(d, 1)) return SOLAR_ERR_UNSUPPORTED;
     Carve c = carve(workspace, B, N, d);
     if (!workspace || workspace_bytes < c.total || ((uintptr_t)workspace & 255)) return SOLAR_ERR_WORKSPACE;
-    hipError_t e = launch_gram(X, lengths, B, N, d, t == SOLAR_BF16, c.partials, G, (hipStream_t)stream);
+    hipError_t e = launch_gram(X, lengths, B, N, d, t == SOLAR_BF16, c.partials, G, true, (hipStream_t)stream);
     return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
 }
 
@@ -134,10 +134,13 @@ solar_status solar_svd_factorize(const void* X, const int32_t* lengths, int B, i
     const bool bf16 = t == SOLAR_BF16;
     const int call = g_timer.calls;
     timer_mark(call, 0, st);
-    hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, st);
+    // where the eigen-iteration can sum the split-N partial blocks itself, G is never formed
+    const bool fused = gram_partials_consumable(d) && !std::getenv("SOLAR_GRAM_FINALIZE");
+    hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, !fused, st);
     if (e != hipSuccess) return SOLAR_ERR_HIP;
     timer_mark(call, 1, st);
-    e = launch_eig(c.G, lengths, B, N, d, r, S, V, info, eig_params_from_env(), st);
+    e = launch_eig(c.G, fused ? c.partials : nullptr, gram_nsplit(B, N), lengths, B, N, d, r, S, V, info,
+                   eig_params_from_env(), st);
     if (e != hipSuccess) return SOLAR_ERR_HIP;
     timer_mark(call, 2, st);
     if (P) {
@@ -203,7 +206,7 @@ solar_status solar_linear_attention(const void* Q, const void* X, const int32_t*
     if (!workspace || workspace_bytes < c.total || ((uintptr_t)workspace & 255)) return SOLAR_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const bool bf16 = t == SOLAR_BF16;
-    hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, st);
+    hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, true, st);
     if (e != hipSuccess) return SOLAR_ERR_HIP;
     e = launch_rowgemm(Q, c.G, (size_t)d * d, B, M, d, scale, bf16, false, O, st);
     return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;

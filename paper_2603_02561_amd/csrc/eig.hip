@@ -274,7 +274,8 @@ __device__ __forceinline__ void mgs_orthonormalize(float* Zc, float* Qc, float d
 
 template <int D, int L>
 __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
-    const float* __restrict__ G, const int32_t* __restrict__ lengths, int N, int r,
+    const float* __restrict__ G, const float* __restrict__ partials, int nsplit,
+    const int32_t* __restrict__ lengths, int N, int r,
     float* __restrict__ S, float* __restrict__ V, int32_t* __restrict__ info, EigParams prm) {
     using C = EigCfg<D, L>;
     constexpr int LP = C::LP, LD = C::LD, TC = C::TC;
@@ -302,9 +303,58 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     }
     if (tid == 0) { sh_bits = 0; sh_bits2 = 0; }
     if constexpr (C::GLDS) {
-        for (int e = tid; e < D * D / 4; e += kEigThreads) {
-            const int i = e / (D / 4), c4 = e % (D / 4);
-            *reinterpret_cast<v4f*>(Gs + i * C::GS + 4 * c4) = *reinterpret_cast<const v4f*>(Gb + (size_t)i * D + 4 * c4);
+        if (partials) {
+            // G from the split-N partial blocks of the Gram kernel: per chunk and fragment pair
+            // (s1 <= s2 of CPL = D/16 column fragments) a 16 x 16 block in MFMA layout, lane
+            // i2 + 16*(i1/4), component i1%4, holding G[CPL*i1 + s1][CPL*i2 + s2]; pairs with
+            // s1 < s2 also supply the mirror image.  Chunks are summed in a fixed order.
+            constexpr int CPL = D / 16, NP = CPL * (CPL + 1) / 2;
+            const float* pb = partials + (size_t)b * nsplit * (NP * 256);
+            // all loads of four chunks are issued before the first is used: the blocks were
+            // written by other compute units and come from beyond this XCD's L2
+            constexpr int ITEMS = (NP * 64 + kEigThreads - 1) / kEigThreads;
+            v4f acc[ITEMS];
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
+            for (int sp0 = 0; sp0 < nsplit; sp0 += 4) {
+                v4f part[4][ITEMS];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int i = 0; i < ITEMS; ++i) {
+                        const int e = tid + i * kEigThreads;
+                        const bool on = e < NP * 64 && sp0 + q < nsplit;
+                        part[q][i] = on ? *reinterpret_cast<const v4f*>(pb + (size_t)(sp0 + q) * (NP * 256) + e * 4)
+                                        : v4f{0.f, 0.f, 0.f, 0.f};
+                    }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int i = 0; i < ITEMS; ++i) acc[i] += part[q][i];
+            }
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {
+                const int e = tid + i * kEigThreads;
+                if (e < NP * 64) {
+                    const int pair = e >> 6, ln = e & 63;
+                    int s1 = 0, rest = pair;
+                    while (rest >= CPL - s1) { rest -= CPL - s1; ++s1; }
+                    const int s2 = s1 + rest;
+                    const int c = CPL * (ln & 15) + s2;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int a = CPL * (4 * (ln >> 4) + t) + s1;
+                        Gs[a * C::GS + c] = acc[i][t];
+                        if (s1 < s2) Gs[c * C::GS + a] = acc[i][t];
+                    }
+                }
+            }
+        } else {
+            for (int e = tid; e < D * D / 4; e += kEigThreads) {
+                const int i = e / (D / 4), c4 = e % (D / 4);
+                *reinterpret_cast<v4f*>(Gs + i * C::GS + 4 * c4) =
+                    *reinterpret_cast<const v4f*>(Gb + (size_t)i * D + 4 * c4);
+            }
         }
     }
     const float* Gop = C::GLDS ? Gs : Gb;
@@ -597,26 +647,27 @@ hipError_t launch_rsvd_small_t(const float* W, const float* Gy, const int32_t* l
 }
 
 template <int D, int L>
-hipError_t launch_eig_t(const float* G, const int32_t* lengths, int B, int N, int r, float* S,
-                        float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
+hipError_t launch_eig_t(const float* G, const float* partials, int nsplit, const int32_t* lengths, int B, int N,
+                        int r, float* S, float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
+    if (partials && !EigCfg<D, L>::GLDS) return hipErrorInvalidValue;
     const size_t lds = sizeof(float) * EigCfg<D, L>::lds_floats;
     auto kern = eig_topr_kernel<D, L>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(B), dim3(kEigThreads), lds, stream, G, lengths, N, r, S, V, info,
-                       prm);
+    hipLaunchKernelGGL(kern, dim3(B), dim3(kEigThreads), lds, stream, G, partials, nsplit, lengths, N, r, S, V,
+                       info, prm);
     return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_eig_d(const float* G, const int32_t* lengths, int B, int N, int r, float* S,
-                        float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
+hipError_t launch_eig_d(const float* G, const float* partials, int nsplit, const int32_t* lengths, int B, int N,
+                        int r, float* S, float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
     const int L = eig_block_columns(D, r);
 #define SOLAR_EIG_CASE(LL)                                                                    \
     case LL:                                                                                  \
         if constexpr (LL <= D && (D < 256 || LL <= 40))                                       \
-            return launch_eig_t<D, LL>(G, lengths, B, N, r, S, V, info, prm, stream);         \
+            return launch_eig_t<D, LL>(G, partials, nsplit, lengths, B, N, r, S, V, info, prm, stream); \
         else                                                                                  \
             return hipErrorInvalidValue;
     switch (L) {
@@ -660,12 +711,12 @@ size_t eig_lds_bytes(int d, int r) {
     return sizeof(float) * ((size_t)2 * LP * (d + 4) + 3 * LP + 8 + (d <= 128 ? (size_t)d * (d + 16) : 0));
 }
 
-hipError_t launch_eig(const float* G, const int32_t* lengths, int B, int N, int d, int r, float* S,
-                      float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
+hipError_t launch_eig(const float* G, const float* partials, int nsplit, const int32_t* lengths, int B, int N,
+                      int d, int r, float* S, float* V, int32_t* info, const EigParams& prm, hipStream_t stream) {
     switch (d) {
-        case 64: return launch_eig_d<64>(G, lengths, B, N, r, S, V, info, prm, stream);
-        case 128: return launch_eig_d<128>(G, lengths, B, N, r, S, V, info, prm, stream);
-        case 256: return launch_eig_d<256>(G, lengths, B, N, r, S, V, info, prm, stream);
+        case 64: return launch_eig_d<64>(G, partials, nsplit, lengths, B, N, r, S, V, info, prm, stream);
+        case 128: return launch_eig_d<128>(G, partials, nsplit, lengths, B, N, r, S, V, info, prm, stream);
+        case 256: return launch_eig_d<256>(G, partials, nsplit, lengths, B, N, r, S, V, info, prm, stream);
         default: return hipErrorInvalidValue;
     }
 }

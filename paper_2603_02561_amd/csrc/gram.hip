@@ -398,7 +398,7 @@ size_t gram_partial_floats(int B, int N, int d) {
 
 template <int CPL>
 static hipError_t launch_gram_t(const void* X, const int32_t* lengths, int B, int N, bool bf16,
-                                float* partials, float* G, hipStream_t stream) {
+                                float* partials, float* G, bool finalize, hipStream_t stream) {
     const int nsplit = gram_nsplit(B, N);
     dim3 grid(nsplit, B), block(kGramWaves * 64);
     if (bf16)
@@ -407,17 +407,22 @@ static hipError_t launch_gram_t(const void* X, const int32_t* lengths, int B, in
     else
         hipLaunchKernelGGL((gram_partial_kernel<CPL, false>), grid, block, 0, stream, X, lengths, N,
                            nsplit, partials);
-    constexpr int D = 16 * CPL;
-    dim3 g2(ceil_div(D * D, 256), B);
-    hipLaunchKernelGGL((gram_finalize_kernel<CPL>), g2, dim3(256), 0, stream, partials, nsplit, G);
+    if (finalize) {
+        constexpr int D = 16 * CPL;
+        dim3 g2(ceil_div(D * D, 256), B);
+        hipLaunchKernelGGL((gram_finalize_kernel<CPL>), g2, dim3(256), 0, stream, partials, nsplit, G);
+    }
     return hipGetLastError();
 }
 
+bool gram_partials_consumable(int d) { return d == 64 || d == 128; }
+
 hipError_t launch_gram(const void* X, const int32_t* lengths, int B, int N, int d, bool bf16,
-                       float* partials, float* G, hipStream_t stream) {
+                       float* partials, float* G, bool finalize, hipStream_t stream) {
+    if (!gram_partials_consumable(d)) finalize = true;
     switch (d) {
-        case 64: return launch_gram_t<4>(X, lengths, B, N, bf16, partials, G, stream);
-        case 128: return launch_gram_t<8>(X, lengths, B, N, bf16, partials, G, stream);
+        case 64: return launch_gram_t<4>(X, lengths, B, N, bf16, partials, G, finalize, stream);
+        case 128: return launch_gram_t<8>(X, lengths, B, N, bf16, partials, G, finalize, stream);
         case 256: {
             const int nsplit = gram_nsplit(B, N);
             dim3 grid(nsplit, B, 4), block(kGramWaves * 64);

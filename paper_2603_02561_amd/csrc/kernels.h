@@ -10,8 +10,11 @@ namespace solar {
 // gram.hip
 int gram_nsplit(int B, int N);
 size_t gram_partial_floats(int B, int N, int d);
+// finalize = false leaves the split-N partial blocks unreduced (G is not written) for a consumer
+// that sums them itself; only honoured where gram_partials_consumable(d)
+bool gram_partials_consumable(int d);
 hipError_t launch_gram(const void* X, const int32_t* lengths, int B, int N, int d, bool bf16,
-                       float* partials, float* G, hipStream_t stream);
+                       float* partials, float* G, bool finalize, hipStream_t stream);
 
 // eig.hip
 struct EigParams {
@@ -25,8 +28,10 @@ struct EigParams {
 EigParams eig_default_params();
 int eig_block_columns(int d, int r);
 size_t eig_lds_bytes(int d, int r);
-hipError_t launch_eig(const float* G, const int32_t* lengths, int B, int N, int d, int r, float* S,
-                      float* V, int32_t* info, const EigParams& prm, hipStream_t stream);
+// partials != nullptr (with nsplit blocks per user, the layout gram_partial_kernel writes):
+// G is not read, the kernel sums the partial blocks itself
+hipError_t launch_eig(const float* G, const float* partials, int nsplit, const int32_t* lengths, int B, int N,
+                      int d, int r, float* S, float* V, int32_t* info, const EigParams& prm, hipStream_t stream);
 
 hipError_t launch_rsvd_small(const float* W, const float* Gy, const int32_t* lengths, int B, int N, int d,
                              int r, float* S, float* V, int32_t* info, hipStream_t stream);
