@@ -163,16 +163,17 @@ def main() -> int:
         del src, dst
     w = synth.make_config(args.workload)
     bf16 = w.dtype == synth.BF16
-    sets = [binding.DeviceBatch(w.X, w.Q, w.lengths, w.r, bf16) for _ in range(N_BUFFER_SETS)]
+    n_sets = max(N_BUFFER_SETS, args.streams)   # one buffer set per batch in flight
+    sets = [binding.DeviceBatch(w.X, w.Q, w.lengths, w.r, bf16) for _ in range(n_sets)]
     scale = 1.0
     # Steps are independent batches.  Step i runs on stream i % n_streams with buffer set
-    # i % N_BUFFER_SETS (its own inputs, outputs and workspace), so the latency-bound
+    # i % n_sets (its own inputs, outputs and workspace), so the latency-bound
     # eigen-iteration of one batch overlaps the bandwidth/ALU-bound phases of its neighbours.
-    n_streams = max(1, min(args.streams, N_BUFFER_SETS))
+    n_streams = max(1, min(args.streams, n_sets))
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
 
     def step(i):
-        db = sets[i % N_BUFFER_SETS]
+        db = sets[i % n_sets]
         with torch.cuda.stream(streams[i % n_streams]):
             db.factorize()
             db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
@@ -193,7 +194,7 @@ def main() -> int:
     with torch.cuda.stream(streams[0]):
         ser_start.record()
         for i in range(args.steps):
-            db = sets[i % N_BUFFER_SETS]
+            db = sets[i % n_sets]
             db.factorize()
             ser_ev[i][0].record()
             db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
@@ -217,7 +218,7 @@ def main() -> int:
     for st in streams:
         st.wait_stream(torch.cuda.current_stream())
     for i in range(args.steps):
-        db = sets[i % N_BUFFER_SETS]
+        db = sets[i % n_sets]
         with torch.cuda.stream(streams[i % n_streams]):
             db.factorize()
             attn_ev[i][0].record()
@@ -301,7 +302,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} N={w.N} d={w.d} r={w.r} M={w.M} "
                                f"{'bf16' if bf16 else 'f32'} inputs, mode 0, scale {scale}",
-                   "recipe": w.recipe, "buffer_sets": N_BUFFER_SETS},
+                   "recipe": w.recipe, "buffer_sets": n_sets},
         "phase_ms": phases, "dominant_kernel": dominant, "kernels": kernels,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
         "streams": n_streams, "serial_pass_ms": solo,
@@ -366,7 +367,7 @@ def main() -> int:
         n_cpu = min(args.cpu_users, w.B)
         base, o_cpu = cpu_baseline(w, n_cpu)
         out["cpu_baseline"] = base
-        o_gpu = sets[(args.steps - 1) % N_BUFFER_SETS].O[:n_cpu].cpu().numpy().astype(np.float64)
+        o_gpu = sets[(args.steps - 1) % n_sets].O[:n_cpu].cpu().numpy().astype(np.float64)
         err = max(float(np.abs(o_gpu[b] - o_cpu[b]).max() / np.abs(o_cpu[b]).max()) for b in range(n_cpu))
         out["max_rel_err_vs_oracle"] = err
     print(json.dumps(out))
