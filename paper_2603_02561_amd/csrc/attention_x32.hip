@@ -9,7 +9,7 @@
 //   * 32x32x16 products: one instruction covers 1024 scores where the 16x16x32 shape covers
 //     256, so a block of 32 rows of P against 32 queries costs two MFMAs for the scores and
 //     two for Z^T += P^T W^T;
-//   * row sums of the rounded weights by one more MFMA per 16 rows against a tile of ones:
+//   * row sums of the rounded weights by one more (16x16x32) MFMA per 16 rows against ones:
 //     it costs the issue port a fraction of what a chain of dependent vector adds or packed
 //     dot products costs (their result latency is exposed), and the matrix pipe has room;
 //   * the softmax reference is not maintained at all on the first, optimistic pass over the
@@ -75,6 +75,11 @@ typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ v16f mma32(v4u a, v4u b, v16f c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c,
+                                                  0, 0, 0);
+}
+
+__device__ __forceinline__ v4f mma16(v4u a, v4u b, v4f c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c,
                                                   0, 0, 0);
 }
 
@@ -230,13 +235,20 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     v4u wp[2][2];       // packed weights [block parity][chunk]
     v16f z;             // Z^T, rank 8*(t/4) + 4*h + t%4 of query n32
     v16f cinit;         // -mref in every register: start value of the score accumulators
-    v16f lacc;          // row sum of the weights of query n32 in every register
+    v4f lacc;           // row sums of the weights: lanes 0..15 hold query `lane` in component 0 and
+                        // query `lane + 16` in component 1 (rows 0 and 1 of a 16x16 product)
     float mref = 0.f;
     float smax = 0.f;   // guarded pass: largest score of the lane in the block that is exponentiated next
-    const v4u ones = v4u{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};   // eight fp16 ones
+    // A operand of the row-sum product (16x16x32: contraction slot 8*(l/16) + e, result row l%16):
+    // row 0 takes the slots of the lane groups that hold queries 0..15 (even l/16), row 1 those of
+    // queries 16..31; every other row is zero
+    const bool sel = ((lane & 15) == 0 && ((lane >> 4) & 1) == 0) || ((lane & 15) == 1 && ((lane >> 4) & 1) == 1);
+    const uint32_t one2 = sel ? 0x3c003c00u : 0u;   // two fp16 ones
+    const v4u ones = v4u{one2, one2, one2, one2};
     auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < 16; ++t) { z[t] = 0.f; cinit[t] = 0.f; lacc[t] = 0.f; }
+        for (int t = 0; t < 16; ++t) { z[t] = 0.f; cinit[t] = 0.f; }
+        lacc = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             wp[0][c] = wp[1][c] = v4u{0u, 0u, 0u, 0u};
@@ -255,12 +267,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // everything that is relative to the reference moves with it by shift (log2 units)
     auto apply_shift = [&](int cur, float shift, float alpha) __attribute__((always_inline)) {
         mref += shift;
+        lacc[0] *= alpha;                                   // lanes 0..15: their own query
+        lacc[1] *= __shfl(alpha, (lane & 15) + 16);         // and the query 16 lanes up
         const _Float16 ah = (_Float16)alpha;
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
             s[cur][t] -= shift;
             z[t] *= alpha;
-            lacc[t] *= alpha;
             cinit[t] = -mref;
         }
 #pragma unroll
@@ -359,7 +372,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         __builtin_amdgcn_s_setprio(0);
         SOLAR_FENCE;
         __builtin_amdgcn_s_setprio(1);
-        lacc = mma32(ones, wp[cur][0], lacc);
+        lacc = mma16(ones, wp[cur][0], lacc);
         __builtin_amdgcn_s_setprio(0);
         SOLAR_FENCE;
         E(12); zlo = lds_read_tr16(za_this + 16 * LDR);
@@ -374,7 +387,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         zA[cur][1] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
         SOLAR_FENCE;
         __builtin_amdgcn_s_setprio(1);
-        lacc = mma32(ones, wp[cur][1], lacc);
+        lacc = mma16(ones, wp[cur][1], lacc);
         __builtin_amdgcn_s_setprio(0);
         SOLAR_FENCE;
         X(2); X(3);
@@ -444,7 +457,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     };
     if (__builtin_expect(!guarded_only, 1)) {
         pass(std::false_type{});
-        if (!(lacc[0] < 3.0e38f)) *redo = 1;   // some weight left the fp16 range (or the input is not finite)
+        if (!(lacc[0] < 3.0e38f) || !(lacc[1] < 3.0e38f)) *redo = 1;   // some weight left the fp16 range (or the input is not finite)
     } else if (tid == 0) {
         *redo = 1;
     }
@@ -458,7 +471,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // ---- epilogue in float: O^T = V (Z / l)^T with the 32x32x2 MFMA: step t contracts the
     // ranks of register t (one per lane half) -----------------------------------------------------
     {
-        const float l = lacc[0];
+        const float l0 = __shfl(lacc[0], n32 & 15), l1 = __shfl(lacc[1], n32 & 15);
+        const float l = n32 < 16 ? l0 : l1;
         const float inv = l > 0.f ? punscale / l : 0.f;
 #pragma unroll
         for (int t = 0; t < 16; ++t) z[t] *= inv;
