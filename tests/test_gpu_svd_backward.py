@@ -39,6 +39,8 @@ CASES = [
     ("bf16_d128_r16", synth.make_workload("t", 2, 1000, 128, 16, 8, synth.BF16, "spectrum", 0.7, 0.01, seed=303), 0.0),
     ("f32_d256_r48_guard", synth.make_workload("t", 2, 300, 256, 48, 8, synth.F32, "spectrum", 0.5, 0.0, seed=304),
      1e-3),
+    # V_bar is read from global memory here (V and V_bar do not both fit the small kernel's LDS)
+    ("f32_d256_r64", synth.make_workload("t", 2, 280, 256, 64, 8, synth.F32, "spectrum", 0.5, 0.01, seed=308), 0.0),
     ("f32_d64_r64_fullrank", synth.make_workload("t", 1, 257, 64, 64, 8, synth.F32, "spectrum", 0.5, 0.02, seed=305),
      0.0),
 ]
