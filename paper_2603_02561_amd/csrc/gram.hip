@@ -27,6 +27,35 @@ template <int CPL>
 __host__ __device__ constexpr int gram_pairs() { return CPL * (CPL + 1) / 2; }
 
 constexpr int kGramWaves = 4;
+// Sum of the accumulators of the workgroup's waves in a fixed order (wave 0 + 1 + 2 + 3, so the
+// result does not depend on timing), then one coalesced store.  Every wave parks its block in its
+// own LDS region (dynamic LDS, kGramWaves * NP KiB), so a single barrier separates the writes
+// from the sums; adding the waves one after another into one region cost four barriers and a
+// quarter of the kernel's time.
+template <int NP>
+__device__ __forceinline__ void reduce_waves_and_store(const v4f (&acc)[NP], v4f* __restrict__ out) {
+    extern __shared__ __attribute__((aligned(16))) v4f red[];   // [kGramWaves][NP * 64]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) red[(wave * NP + p) * 64 + lane] = acc[p];
+    __syncthreads();
+    for (int i = threadIdx.x; i < NP * 64; i += kGramWaves * 64) {
+        v4f v = red[i];
+#pragma unroll
+        for (int w = 1; w < kGramWaves; ++w) v += red[w * NP * 64 + i];
+        out[i] = v;
+    }
+}
+
+template <int NP>
+constexpr size_t gram_reduce_lds() { return sizeof(v4f) * kGramWaves * NP * 64; }
+
+template <typename K>
+static hipError_t gram_allow_lds(K kern, size_t bytes) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)bytes);
+}
+
 #ifndef SOLAR_GRAM_RING
 #define SOLAR_GRAM_RING 3
 #endif
@@ -179,20 +208,8 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
         }
     }
 
-    // Fixed-order sum over the waves of the workgroup, then one coalesced store.
-    __shared__ v4f red[NP * 64];
-    for (int w = 0; w < kGramWaves; ++w) {
-        if (wave == w) {
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                if (w == 0) red[p * 64 + lane] = acc[p];
-                else red[p * 64 + lane] += acc[p];
-            }
-        }
-        __syncthreads();
-    }
     v4f* out = reinterpret_cast<v4f*>(partials) + ((size_t)b * nsplit + split) * (NP * 64);
-    for (int i = threadIdx.x; i < NP * 64; i += kGramWaves * 64) out[i] = red[i];
+    reduce_waves_and_store<NP>(acc, out);
 }
 
 // G[b][a][c] = sum over chunks of the partial block element that holds (a, c) or,
@@ -329,19 +346,8 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram256_partial_kernel(
         }
     }
 
-    __shared__ v4f red[NP * 64];
-    for (int w = 0; w < kGramWaves; ++w) {
-        if (wave == w) {
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                if (w == 0) red[p * 64 + lane] = acc[p];
-                else red[p * 64 + lane] += acc[p];
-            }
-        }
-        __syncthreads();
-    }
     v4f* out = reinterpret_cast<v4f*>(partials) + (((size_t)b * nsplit + split) * 4 + job) * (NP * 64);
-    for (int i = threadIdx.x; i < NP * 64; i += kGramWaves * 64) out[i] = red[i];
+    reduce_waves_and_store<NP>(acc, out);
 }
 
 __global__ __launch_bounds__(256) void gram256_finalize_kernel(const float* __restrict__ partials,
@@ -401,11 +407,15 @@ static hipError_t launch_gram_t(const void* X, const int32_t* lengths, int B, in
                                 float* partials, float* G, bool finalize, hipStream_t stream) {
     const int nsplit = gram_nsplit(B, N);
     dim3 grid(nsplit, B), block(kGramWaves * 64);
+    constexpr size_t lds = gram_reduce_lds<gram_pairs<CPL>()>();
+    hipError_t e = bf16 ? gram_allow_lds(gram_partial_kernel<CPL, true>, lds)
+                        : gram_allow_lds(gram_partial_kernel<CPL, false>, lds);
+    if (e != hipSuccess) return e;
     if (bf16)
-        hipLaunchKernelGGL((gram_partial_kernel<CPL, true>), grid, block, 0, stream, X, lengths, N,
+        hipLaunchKernelGGL((gram_partial_kernel<CPL, true>), grid, block, lds, stream, X, lengths, N,
                            nsplit, partials);
     else
-        hipLaunchKernelGGL((gram_partial_kernel<CPL, false>), grid, block, 0, stream, X, lengths, N,
+        hipLaunchKernelGGL((gram_partial_kernel<CPL, false>), grid, block, lds, stream, X, lengths, N,
                            nsplit, partials);
     if (finalize) {
         constexpr int D = 16 * CPL;
@@ -426,11 +436,15 @@ hipError_t launch_gram(const void* X, const int32_t* lengths, int B, int N, int 
         case 256: {
             const int nsplit = gram_nsplit(B, N);
             dim3 grid(nsplit, B, 4), block(kGramWaves * 64);
+            constexpr size_t lds = gram_reduce_lds<kGram256Pairs>();
+            hipError_t e = bf16 ? gram_allow_lds(gram256_partial_kernel<true>, lds)
+                                : gram_allow_lds(gram256_partial_kernel<false>, lds);
+            if (e != hipSuccess) return e;
             if (bf16)
-                hipLaunchKernelGGL((gram256_partial_kernel<true>), grid, block, 0, stream, X, lengths, N,
+                hipLaunchKernelGGL((gram256_partial_kernel<true>), grid, block, lds, stream, X, lengths, N,
                                    nsplit, partials);
             else
-                hipLaunchKernelGGL((gram256_partial_kernel<false>), grid, block, 0, stream, X, lengths, N,
+                hipLaunchKernelGGL((gram256_partial_kernel<false>), grid, block, lds, stream, X, lengths, N,
                                    nsplit, partials);
             hipLaunchKernelGGL(gram256_finalize_kernel, dim3(256 * 256 / 256, B), dim3(256), 0, stream,
                                partials, nsplit, G);
