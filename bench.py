@@ -133,6 +133,9 @@ def main() -> int:
     ap.add_argument("--alg1", action="store_true",
                     help="also time the factorization by Algorithm 1 run as printed (passes over X) "
                          "with 0 and 1 power iterations, next to the Gram route")
+    ap.add_argument("--from-x", action="store_true",
+                    help="time the variant that never stores P: solar_svd_factorize with P = NULL and "
+                         "solar_svd_attention_from_x (the projection inside the attention kernel)")
     ap.add_argument("--backward", action="store_true",
                     help="also time the gradient through the factorization (dL/dX from dL/dS, dL/dV)")
     ap.add_argument("--sweep", action="store_true",
@@ -172,11 +175,18 @@ def main() -> int:
     n_streams = max(1, min(args.streams, n_sets))
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
 
+    if args.from_x:
+        def factorize(db): db.factorize_no_p()
+        def attend(db): db.attention_from_x(scale)
+    else:
+        def factorize(db): db.factorize()
+        def attend(db): db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
+
     def step(i):
         db = sets[i % n_sets]
         with torch.cuda.stream(streams[i % n_streams]):
-            db.factorize()
-            db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
+            factorize(db)
+            attend(db)
 
     for i in range(max(args.warmup, 1)):
         step(i)
@@ -195,9 +205,9 @@ def main() -> int:
         ser_start.record()
         for i in range(args.steps):
             db = sets[i % n_sets]
-            db.factorize()
+            factorize(db)
             ser_ev[i][0].record()
-            db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
+            attend(db)
             ser_ev[i][1].record()
         ser_stop.record()
     torch.cuda.synchronize()
@@ -220,9 +230,9 @@ def main() -> int:
     for i in range(args.steps):
         db = sets[i % n_sets]
         with torch.cuda.stream(streams[i % n_streams]):
-            db.factorize()
+            factorize(db)
             attn_ev[i][0].record()
-            db.attention(scale, binding.SOLAR_ATTN_SEQ_SOFTMAX)
+            attend(db)
             attn_ev[i][1].record()
     for st in streams:
         torch.cuda.current_stream().wait_stream(st)

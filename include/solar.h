@@ -116,6 +116,24 @@ solar_status solar_svd_attention(const void* Q, const float* S, const float* V, 
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Mode 0 of the attention step with the projection fused into it: P = X V (Section
+ * "SVD-Attention", the product U Sigma that replaces U) is formed tile by tile inside the attention
+ * kernel and never written, so solar_svd_factorize can be called with P = NULL:
+ *   O = softmax_n(scale * (Q V) (X V)^T) (X V) V^T   over the rows n < lengths[b].
+ * Every workgroup of a user repeats that user's projection (ceil(M/256) times in all); the call
+ * pays when the factors are used for one candidate set, solar_svd_attention with a stored P when
+ * they are used for many.
+ *   Q  in [B,M,d] bf16     X  in [B,N,d] bf16     S, V  in  as written by solar_svd_factorize
+ *   O  out [B,M,d] float
+ * Supported: t = SOLAR_BF16, d in {64, 128, 256}, r <= 32 and a multiple of 4; anything else
+ * returns SOLAR_ERR_UNSUPPORTED.  No workspace is used.
+ */
+solar_status solar_svd_attention_from_x(const void* Q, const void* X, const float* S, const float* V,
+                                        const int32_t* lengths, int B, int N, int d, int r, int M,
+                                        float scale, solar_dtype t, float* O, void* workspace,
+                                        size_t workspace_bytes, void* stream);
+
+/*
  * Dense softmax attention over the raw sequence (Preliminaries, Attn_sm with
  * Key = Value = X): O = softmax_n(scale * Q X^T) X over the valid rows.  A
  * straightforward float kernel kept as the on-device reference for what

@@ -40,6 +40,9 @@ _lib.solar_svd_factorize.restype = _ci
 _lib.solar_svd_attention.argtypes = [_vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _cf, _ci,
                                      _ci, _vp, _vp, _sz, _vp]
 _lib.solar_svd_attention.restype = _ci
+_lib.solar_svd_attention_from_x.argtypes = [_vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _cf, _ci, _vp, _vp,
+                                            _sz, _vp]
+_lib.solar_svd_attention_from_x.restype = _ci
 _lib.solar_dense_attention_ref.argtypes = [_vp, _vp, _vp, _ci, _ci, _ci, _ci, _cf, _ci, _vp, _vp,
                                            _sz, _vp]
 _lib.solar_dense_attention_ref.restype = _ci
@@ -160,6 +163,18 @@ def solar_svd_attention(Q, S, V, P, lengths, N: int, scale: float, mode: int, O,
     return rc
 
 
+def solar_svd_attention_from_x(Q, X, S, V, lengths, scale: float, O, raise_on_error: bool = True) -> int:
+    _check(Q, X, S, V, lengths, O)
+    B, M, d = Q.shape
+    N = X.shape[1]
+    r = V.shape[2]
+    rc = _lib.solar_svd_attention_from_x(_ptr(Q), _ptr(X), _ptr(S), _ptr(V), _ptr(lengths), B, N, d, r, M,
+                                         float(scale), _dtype_code(Q), _ptr(O), None, 0, _stream())
+    if rc != SOLAR_OK and raise_on_error:
+        raise SolarError(rc)
+    return rc
+
+
 def solar_dense_attention_ref(Q, X, lengths, scale: float, O, workspace=None,
                               raise_on_error: bool = True) -> int:
     _check(Q, X, lengths, O, workspace)
@@ -261,6 +276,15 @@ class DeviceBatch:
             dX = torch.empty((self.B, self.N, self.d), dtype=torch.float32, device=self.X.device)
         solar_svd_backward(self.S, self.V, self.P, S_bar, V_bar, gap_rel, dX, self.workspace)
         return dX
+
+    def attention_from_x(self, scale: float, O=None):
+        """Mode 0 with P = X V formed inside the attention kernel (bf16 inputs, r <= 32)."""
+        return solar_svd_attention_from_x(self.Q, self.X, self.S, self.V, self.lengths, scale,
+                                          self.O if O is None else O)
+
+    def factorize_no_p(self):
+        return solar_svd_factorize(self.X, self.lengths, self.r, self.S, self.V, None, self.info,
+                                   self.workspace)
 
     def linear(self, scale: float, O=None):
         return solar_linear_attention(self.Q, self.X, self.lengths, scale, self.O if O is None else O,

@@ -109,15 +109,20 @@ __device__ __forceinline__ uint2 lds_read_tr16(const uint16_t* p) {
 // of every 16 ranks are swapped
 __device__ __forceinline__ int quad_pos(int c4) { return (c4 & ~3) | ((c4 & 1) << 1) | ((c4 >> 1) & 1); }
 
-template <int D>
+// FUSED: Pin is the user's X (bf16, [B][N][D]) and the loader forms the rows of P = X V itself
+// (the projection of Section "SVD-Attention" evaluated where it is consumed; every workgroup of
+// a user repeats it); otherwise Pin is P (float, [B][N][r]).
+template <int D, bool FUSED>
 __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const void* __restrict__ Qv, const float* __restrict__ S, const float* __restrict__ V,
-    const float* __restrict__ P, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
+    const void* __restrict__ Pin, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
     float scale, int guarded_only, float* __restrict__ O) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                                              // [D][LDV]
     uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);   // [3][kBuf]
     int* redo = reinterpret_cast<int*>(tiles + 3 * kBuf);          // set when a wave's optimistic pass overflowed
+    constexpr int LDVT = D + 8;                                    // bf16 elements
+    uint16_t* vt = reinterpret_cast<uint16_t*>(redo + 4);          // FUSED: [2][RP][LDVT], V^T as bf16 head and tail
     // Workgroups are dealt to the 8 XCDs round-robin by linear id.  All M-tiles of a user
     // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
     const int mtiles = ceil_div(M, kWaves * kQW);
@@ -128,7 +133,6 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const int n32 = lane & 31, h = lane >> 5;
     const int len = user_len(lengths, b, N);
     const int m_wave = (slot_id % mtiles) * (kWaves * kQW) + wave * kQW;
-    const float* Pb = P + (size_t)b * N * r;
     // P is scaled into [-1, 1] by the largest singular value before it is rounded to fp16
     // when that value lies outside [1, 2^13]; inside that range fp16 holds P as it is
     float pscale = 1.f, punscale = 1.f;
@@ -146,6 +150,18 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // zero the tile buffers once: padded rank columns stay zero for ever
     for (int e = tid; e < 3 * kBuf / 2; e += kThreads) reinterpret_cast<uint32_t*>(tiles)[e] = 0u;
     if (tid == 0) *redo = 0;
+    if constexpr (FUSED) {
+        // V^T split into a bf16 head (truncated, so the remainder is exact) and a bf16 tail
+        for (int e = tid; e < RP * D; e += kThreads) {
+            const int c = e / D, k = e % D;
+            const float v = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
+            const uint32_t hi = __float_as_uint(v) & 0xffff0000u;
+            const float rem = v - __uint_as_float(hi);
+            const uint32_t lo = (__float_as_uint(rem) + 0x7fffu + ((__float_as_uint(rem) >> 16) & 1u)) >> 16;
+            vt[c * LDVT + k] = (uint16_t)(hi >> 16);
+            vt[(RP + c) * LDVT + k] = (uint16_t)lo;
+        }
+    }
     __syncthreads();
 
     // ---- prologue: Qt^T = V^T Q^T in float (32x32x2 MFMA; the contraction slot of lane half
@@ -187,29 +203,74 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // tile is converted).  Rank quads at or beyond r load quad r/4-1 and are never stored.
     constexpr int kQuads = RP / 4;
     static_assert((kNT / 2) * kQuads == kThreads, "one loader task per thread");
+    const int nfull = len / kNT;   // tiles whose rows are all valid
+    const int last_row = max(len - 1, 0);   // clamp of the row index of loads past the valid length
+    // -- P given: a thread owns two consecutive rows and four consecutive ranks of a tile
     const int ld_np = tid / kQuads, ld_c4 = tid % kQuads;
     const bool ld_active = 4 * ld_c4 < r;
     const int ld_dst = (2 * ld_np) * LDR + 4 * quad_pos(ld_c4);
-    const uint32_t row_bytes = 4u * (uint32_t)r;
+    const uint32_t row_bytes = FUSED ? 2u * D : 4u * (uint32_t)r;
     const uint32_t ld_col = 16u * (uint32_t)min(ld_c4, (r >> 2) - 1);
-    const int nfull = len / kNT;   // tiles whose rows are all valid
-    const char* Pbytes = reinterpret_cast<const char*>(Pb);
-    uint32_t ld_off = (uint32_t)(2 * ld_np) * row_bytes + ld_col;   // row 2*ld_np of the next tile to fetch
-    v4f stage[2];
-    auto fetch = [&](int tile) __attribute__((always_inline)) {
-        uint32_t o0 = ld_off, o1 = ld_off + row_bytes;
-        if (__builtin_expect(tile >= nfull, 0)) {   // uniform: the ragged last tile
-            const int n0 = min(tile * kNT + 2 * ld_np, len - 1), n1 = min(tile * kNT + 2 * ld_np + 1, len - 1);
-            o0 = (uint32_t)n0 * row_bytes + ld_col;
-            o1 = (uint32_t)n1 * row_bytes + ld_col;
+    // -- X given: wave w owns rows 16*w .. 16*w+15 of a tile; lane (row l%16, group l/16) loads
+    // the quarter l/16 of its row (D/4 consecutive columns), which it supplies as contraction
+    // slots of the products P^T = V^T X^T (16x16x32 bf16: eight columns per lane and step; the
+    // A operand from vt enumerates the columns in the same order)
+    constexpr int KS = D / 32;   // products per rank block
+    const int fx_row = 16 * wave + (lane & 15), fx_g = lane >> 4;
+    const char* Pbytes = reinterpret_cast<const char*>(Pin) +
+                         (FUSED ? (size_t)b * N * (2u * D) + (size_t)fx_g * (D / 2) : (size_t)b * N * (4u * r));
+    const uint32_t ld_off0 = FUSED ? (uint32_t)fx_row * row_bytes : (uint32_t)(2 * ld_np) * row_bytes + ld_col;
+    uint32_t ld_off = ld_off0;   // this thread's first row of the next tile to fetch
+    // two sets of staging registers: a tile is loaded two loop iterations before it is converted,
+    // so that the loads (L2 or HBM) have a whole tile of arithmetic to arrive
+    v4f stage[2][2];
+    v4u xst[2][FUSED ? KS : 1];
+    auto fetch = [&](int tile, auto par_tag) __attribute__((always_inline)) {
+        constexpr int par = decltype(par_tag)::value;
+        if constexpr (FUSED) {
+            uint32_t o0 = ld_off;
+            if (__builtin_expect(tile >= nfull, 0))   // uniform: the ragged last tile
+                o0 = (uint32_t)min(tile * kNT + fx_row, last_row) * row_bytes;
+            const v4u* p = reinterpret_cast<const v4u*>(Pbytes + o0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) xst[par][ks] = p[ks];
+        } else {
+            uint32_t o0 = ld_off, o1 = ld_off + row_bytes;
+            if (__builtin_expect(tile >= nfull, 0)) {   // uniform: the ragged last tile
+                const int n0 = min(tile * kNT + 2 * ld_np, last_row), n1 = min(tile * kNT + 2 * ld_np + 1, last_row);
+                o0 = (uint32_t)n0 * row_bytes + ld_col;
+                o1 = (uint32_t)n1 * row_bytes + ld_col;
+            }
+            stage[par][0] = *reinterpret_cast<const v4f*>(Pbytes + o0);
+            stage[par][1] = *reinterpret_cast<const v4f*>(Pbytes + o1);
         }
-        stage[0] = *reinterpret_cast<const v4f*>(Pbytes + o0);
-        stage[1] = *reinterpret_cast<const v4f*>(Pbytes + o1);
         ld_off += (uint32_t)kNT * row_bytes;
     };
-    auto commit = [&](uint16_t* buf, int tile) __attribute__((always_inline)) {
-        if (ld_active) {
-            v4f x0 = stage[0], x1 = stage[1];
+    auto commit = [&](uint16_t* buf, int tile, auto par_tag) __attribute__((always_inline)) {
+        constexpr int par = decltype(par_tag)::value;
+        if constexpr (FUSED) {
+            // result register t of rank block nb: rank 16*nb + 4*(l/16) + t of row l%16, i.e.
+            // one rank quad of the lane's row
+#pragma unroll
+            for (int nb = 0; nb < RP / 16; ++nb) {
+                v4f pa = v4f{0.f, 0.f, 0.f, 0.f};
+                const uint16_t* va = vt + (16 * nb + (lane & 15)) * LDVT + (D / 4) * fx_g;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    pa = mfma16x16x32bf16(*reinterpret_cast<const v4u*>(va + 8 * ks), xst[par][ks], pa);
+                    pa = mfma16x16x32bf16(*reinterpret_cast<const v4u*>(va + RP * LDVT + 8 * ks), xst[par][ks], pa);
+                }
+                if (__builtin_expect(tile >= nfull, 0)) {   // uniform
+                    if (tile * kNT + fx_row >= len) pa = v4f{0.f, 0.f, 0.f, 0.f};
+                }
+                if (__builtin_expect(rescale, 0)) pa *= pscale;   // uniform
+                const int quad = 4 * nb + fx_g;
+                if (4 * quad < r)
+                    *reinterpret_cast<uint2*>(buf + fx_row * LDR + 4 * quad_pos(quad)) =
+                        uint2{pack_f16(pa[0], pa[1]), pack_f16(pa[2], pa[3])};
+            }
+        } else if (ld_active) {
+            v4f x0 = stage[par][0], x1 = stage[par][1];
             if (__builtin_expect(tile >= nfull, 0)) {   // uniform
                 if (tile * kNT + 2 * ld_np >= len) x0 = v4f{0.f, 0.f, 0.f, 0.f};
                 if (tile * kNT + 2 * ld_np + 1 >= len) x1 = v4f{0.f, 0.f, 0.f, 0.f};
@@ -255,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             zA[0][c] = zA[1][c] = v4u{0u, 0u, 0u, 0u};
         }
         mref = 0.f; smax = 0.f;
-        ld_off = (uint32_t)(2 * ld_np) * row_bytes + ld_col;
+        ld_off = ld_off0;
     };
 
     // Online softmax with a lazily updated reference: weights are exp2(s - mref) and may exceed
@@ -409,8 +470,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     auto pass = [&](auto guard_tag) __attribute__((always_inline)) {
     constexpr bool guarded = decltype(guard_tag)::value;
     reset_state();
-    if (ntiles > 0) { fetch(0); commit(tiles, 0); }
-    if (ntiles > 1) { fetch(1); commit(tiles + kBuf, 1); }
+    if (ntiles > 0) { fetch(0, tag0{}); commit(tiles, 0, tag0{}); }
+    if (ntiles > 1) { fetch(1, tag0{}); commit(tiles + kBuf, 1, tag0{}); }
+    fetch(2, tag0{});
     __syncthreads();
     if (nblocks > 0) {
         // S(0) and the reference of the first block; the score operands of block 1
@@ -429,21 +491,32 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // byte-free rotation of the three tile buffers: element offsets of the tile being
     // multiplied, the next one and the one being converted
     int o_cur = 0, o_nxt = kBuf, o_wr = 2 * kBuf;
-    for (int tile = 0; tile < ntiles; ++tile) {
-        const bool ahead = tile + 2 < ntiles;
-        if (__builtin_expect(ahead, 1)) fetch(tile + 2);
+    // one tile: its four slots, the loads of tile + 3 into the staging set of the other parity and,
+    // half way, the conversion of tile + 2 (loaded an iteration ago) into the free buffer
+    auto run_tile = [&](int tile, auto par_tag) __attribute__((always_inline)) {
+        constexpr int par = decltype(par_tag)::value;
+        // (tiles past the end are loaded from clamped rows and converted into a buffer nobody
+        // reads: the loop body stays free of branches around its loads, so the wait before a
+        // conversion counts the younger loads instead of draining them)
+        fetch(tile + 3, std::integral_constant<int, par ^ 1>{});
         const uint16_t* sa_cur = tiles + o_cur + sa_off;
         const uint16_t* sa_nxt = tiles + o_nxt + sa_off;
         const uint16_t* za_cur = tiles + o_cur + za_off;
         const int j0 = tile * kNB;
         slot(j0, tag0{}, guard_tag, sa_cur + 2 * 32 * LDR, za_cur);
         if (__builtin_expect(j0 + 1 < nblocks, 1)) slot(j0 + 1, tag1{}, guard_tag, sa_cur + 3 * 32 * LDR, za_cur + 32 * LDR);
-        if (__builtin_expect(ahead, 1)) commit(tiles + o_wr, tile + 2);
+        commit(tiles + o_wr, tile + 2, par_tag);
         if (__builtin_expect(j0 + 2 < nblocks, 1)) slot(j0 + 2, tag0{}, guard_tag, sa_nxt, za_cur + 2 * 32 * LDR);
         if (__builtin_expect(j0 + 3 < nblocks, 1)) slot(j0 + 3, tag1{}, guard_tag, sa_nxt + 32 * LDR, za_cur + 3 * 32 * LDR);
         __syncthreads();
         const int o = o_cur; o_cur = o_nxt; o_nxt = o_wr; o_wr = o;
+    };
+    int tile = 0;
+    for (; tile + 1 < ntiles; tile += 2) {
+        run_tile(tile, tag0{});
+        run_tile(tile + 1, tag1{});
     }
+    if (tile < ntiles) run_tile(tile, tag0{});
     // Z of the last block trails the loop
     if (nblocks > 0) {
         if ((nblocks - 1) & 1) {
@@ -495,14 +568,15 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     }
 }
 
-template <int D>
-hipError_t launch_d(const void* Q, const float* S, const float* V, const float* P, const int32_t* lengths,
+template <int D, bool FUSED>
+hipError_t launch_d(const void* Q, const float* S, const float* V, const void* P, const int32_t* lengths,
                     int B, int N, int r, int M, float scale, float* O, hipStream_t stream) {
     // debugging aid: skip the optimistic pass
     const int guarded_only = std::getenv("SOLAR_X32_GUARDED") != nullptr;
-    const size_t lds = sizeof(float) * (size_t)D * LDV + sizeof(uint16_t) * 3 * (size_t)kBuf + 16;
+    const size_t lds = sizeof(float) * (size_t)D * LDV + sizeof(uint16_t) * 3 * (size_t)kBuf + 16 +
+                       (FUSED ? sizeof(uint16_t) * 2 * RP * (size_t)(D + 8) : 0);
     dim3 grid(ceil_div(M, kWaves * kQW) * 8 * ceil_div(B, 8)), block(kThreads);
-    auto kern = attention_seq_x32_kernel<D>;
+    auto kern = attention_seq_x32_kernel<D, FUSED>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -521,9 +595,21 @@ hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* 
                                     const int32_t* lengths, int B, int N, int d, int r, int M, float scale,
                                     float* O, hipStream_t stream) {
     switch (d) {
-        case 64: return launch_d<64>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
-        case 128: return launch_d<128>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
-        case 256: return launch_d<256>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 64: return launch_d<64, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 128: return launch_d<128, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 256: return launch_d<256, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// The same with the projection P = X V formed inside the kernel: X and Q are bf16.
+hipError_t launch_attention_seq_x32_from_x(const void* Q, const float* S, const float* V, const void* X,
+                                           const int32_t* lengths, int B, int N, int d, int r, int M, float scale,
+                                           float* O, hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_d<64, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
+        case 128: return launch_d<128, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
+        case 256: return launch_d<256, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
         default: return hipErrorInvalidValue;
     }
 }

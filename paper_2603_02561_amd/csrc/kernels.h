@@ -67,6 +67,11 @@ hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* 
                                     const int32_t* lengths, int B, int N, int d, int r, int M,
                                     float scale, float* O, hipStream_t stream);
 
+// the same kernel with P = X V formed inside it (X and Q bf16)
+hipError_t launch_attention_seq_x32_from_x(const void* Q, const float* S, const float* V, const void* X,
+                                           const int32_t* lengths, int B, int N, int d, int r, int M,
+                                           float scale, float* O, hipStream_t stream);
+
 // linear.hip
 hipError_t launch_rowgemm(const void* In, const float* W, size_t w_stride, int B, int rows, int d, float scale,
                           bool in_bf16, bool out_bf16, void* Out, hipStream_t stream);
