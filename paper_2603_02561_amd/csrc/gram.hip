@@ -98,24 +98,15 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
                 }
             }
         };
-        // a step whose 32 rows are all valid issues its eight loads back to back; only the
-        // ragged last step of a chunk pays for per-row predicates
+        // Loads carry no predicate and sit behind no branch: the row index is clamped to the
+        // chunk's last row (rows past it are zeroed when a ragged block is multiplied).  With a
+        // branch around a prefetch the compiler cannot count the loads that are younger than the
+        // block it is about to use and waits for all of them, which undoes the prefetch.
+        const int row_max = max(r1 - 1, 0);
         auto load = [&](uint32_t (&dst)[8][W], int base) __attribute__((always_inline)) {
-            const uint32_t* p0 = X + (size_t)(base + 8 * h) * (D / 2) + W * j;
-            if (base + STEP <= r1) {
 #pragma unroll
-                for (int t = 0; t < 8; ++t) load_row(dst[t], p0 + (size_t)t * (D / 2));
-            } else {
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const bool ok = base + 8 * h + t < r1;
-                    load_row(dst[t], ok ? p0 + (size_t)t * (D / 2) : X);
-                    if (!ok) {
-#pragma unroll
-                        for (int w = 0; w < W; ++w) dst[t][w] = 0u;
-                    }
-                }
-            }
+            for (int t = 0; t < 8; ++t)
+                load_row(dst[t], X + (size_t)min(base + 8 * h + t, row_max) * (D / 2) + W * j);
         };
         auto compute = [&](const uint32_t (&src)[8][W]) __attribute__((always_inline)) {
             // 8x(2W) transpose of 16-bit elements: fragment s holds column CPL*j+s of the
@@ -139,26 +130,43 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
                     ++p;
                 }
         };
+        // a block of the tail: rows at or past the end of the chunk count as zero
+        auto compute_tail = [&](uint32_t (&src)[8][W], int base) __attribute__((always_inline)) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                if (base + 8 * h + t >= r1) {
+#pragma unroll
+                    for (int w = 0; w < W; ++w) src[t][w] = 0u;
+                }
+            compute(src);
+        };
         // ring of kRing row blocks per wave: kRing-1 blocks of loads stay in flight while one
-        // block is multiplied, with the ring index fixed at compile time by the unrolling
+        // block is multiplied, with the ring index fixed at compile time by the unrolling.  The
+        // steady-state loop takes kRing whole blocks per trip and has no branch in its body; at
+        // most kRing - 1 whole blocks and one ragged block are left for the tail.
         constexpr int kRing = SOLAR_GRAM_RING;
         uint32_t ring[kRing][8][W];
         constexpr int stride = kGramWaves * STEP;
-        int base = r0 + wave * STEP;
+        const int base0 = r0 + wave * STEP;
+        const int nblk = base0 < r1 ? ceil_div(r1 - base0, stride) : 0;              // blocks of this wave
+        const int nwhole = r1 - base0 >= STEP ? (r1 - base0 - STEP) / stride + 1 : 0;  // of which whole
 #pragma unroll
-        for (int k = 0; k < kRing - 1; ++k)
-            if (base + k * stride < r1) load(ring[k], base + k * stride);
-        bool more = base < r1;
-        while (more) {
+        for (int k = 0; k < kRing - 1; ++k) load(ring[k], base0 + k * stride);
+        int i = 0;
+        for (; i + kRing <= nwhole; i += kRing) {
 #pragma unroll
             for (int k = 0; k < kRing; ++k) {
-                if (more) {
-                    const int ahead = base + (kRing - 1) * stride;
-                    if (ahead < r1) load(ring[(k + kRing - 1) % kRing], ahead);
-                    compute(ring[k]);
-                    base += stride;
-                    more = base < r1;
-                }
+                load(ring[(k + kRing - 1) % kRing], base0 + (i + k + kRing - 1) * stride);
+                __builtin_amdgcn_sched_barrier(0);   // the prefetch is issued before the block is used
+                compute(ring[k]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kRing; ++k) {
+            if (i + k < nblk) {
+                if (i + k + kRing - 1 < nblk) load(ring[(k + kRing - 1) % kRing], base0 + (i + k + kRing - 1) * stride);
+                compute_tail(ring[k], base0 + (i + k) * stride);
             }
         }
     } else {
