@@ -26,9 +26,9 @@ N_BUFFER_SETS = 3   # rotate inputs so that X is not served from the 256 MiB Inf
 # profiles/ for the commands and the copy-kernel calibration); keyed by (workload, phase).
 MEASURED_TRAFFIC = {
     # profiles/hbm_traffic_C3.txt: fetch + write bytes of one launch
-    ("C3", "attention"): 99.5e6 + 32.8e6,
+    ("C3", "attention"): 99.6e6 + 32.8e6,
     ("C3", "gram"): 164.1e6 + 9.4e6,
-    ("C3", "project"): 172.6e6 + 82.6e6,
+    ("C3", "project"): 172.6e6 + 82.5e6,
 }
 
 PEAKS = {
