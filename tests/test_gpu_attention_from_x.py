@@ -82,3 +82,32 @@ def test_from_x_without_stored_p_and_unsupported(lib, oracle):
     assert lib.solar_svd_attention_from_x(d64.Q, d64.X, d64.S, d64.V, d64.lengths, 1.0, d64.O,
                                           raise_on_error=False) == 2
     torch.cuda.synchronize()
+
+
+def test_valid_lengths_across_tile_boundaries(lib, oracle):
+    """One batch whose users have valid lengths on both sides of every boundary the kernel's
+    sequence loop has (32-row blocks, 128-row tiles, the pairs of tiles of its unrolled loop, and
+    the first three tiles that its prologue loads): both entry points against the oracle."""
+    import torch
+    lens = [8, 31, 32, 33, 96, 127, 128, 129, 160, 255, 256, 257, 383, 384, 385, 511, 512, 513, 640, 641]
+    N, d, r, M = 641, 64, 8, 40
+    w = synth.make_workload("t", len(lens), N, d, r, M, synth.BF16, "gauss_lowrank", seed=505)
+    w.lengths = np.asarray(lens, dtype=np.int32)
+    print("[case] lengths across tile boundaries", flush=True)
+    db = lib.DeviceBatch(w.X, w.Q, w.lengths, r, True)
+    db.factorize()
+    torch.cuda.synchronize()
+    assert np.all(db.info.cpu().numpy() == 0)
+    f = oracle.svd_factorize(w.X, r, w.lengths)
+    O2 = torch.empty_like(db.O)
+    for scale in (1.0, w.sharp_scale):
+        db.attention(scale, 0)
+        db.attention_from_x(scale, O2)
+        torch.cuda.synchronize()
+        want = oracle.svd_attention(w.Q, w.X, f["S"], f["V"], scale, 0, w.lengths)
+        for name, got in (("stored P", db.O), ("from X", O2)):
+            g = got.cpu().numpy().astype(np.float64)
+            errs = [np.abs(g[b] - want[b]).max() / np.abs(want[b]).max() for b in range(len(lens))]
+            worst = int(np.argmax(errs))
+            print(f"  {name} scale={scale:.3g} worst err {max(errs):.3e} at length {lens[worst]}", flush=True)
+            assert max(errs) < 2e-2
