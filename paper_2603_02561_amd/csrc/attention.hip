@@ -24,7 +24,6 @@ namespace solar {
 namespace {
 
 constexpr int kAttnThreads = 256;
-constexpr int kQB = 2;    // 16-query blocks per wave
 constexpr int kNT = 64;   // rows of P per tile
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -34,7 +33,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 // is reused as a B operand, which keeps those reads free of bank conflicts.
 __device__ __forceinline__ int rank_perm(int i) { return (i >> 2) + 4 * (i & 3); }
 
-template <int D, int RB, bool BF16>
+template <int D, int RB, bool BF16, int QB>
 __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
     const void* __restrict__ Qv, const float* __restrict__ V, const float* __restrict__ P,
     const int32_t* __restrict__ lengths, int B, int N, int r, int M, float scale, float* __restrict__ O) {
@@ -46,14 +45,14 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
     float* Ps = Vs + D * LDV;               // [2][kNT][LDP]
     // Workgroups are dealt to the 8 XCDs round-robin by linear id.  All M-tiles of a user
     // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
-    const int mtiles = ceil_div(M, 4 * kQB * 16);
+    const int mtiles = ceil_div(M, 4 * QB * 16);
     const int slot = blockIdx.x >> 3;
     const int b = (slot / mtiles) * 8 + (blockIdx.x & 7);
     if (b >= B) return;   // uniform over the workgroup
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, g = lane >> 4;
     const int len = user_len(lengths, b, N);
-    const int m_wave = (slot % mtiles) * (4 * kQB * 16) + wave * (kQB * 16);
+    const int m_wave = (slot % mtiles) * (4 * QB * 16) + wave * (QB * 16);
     const float* Pb = P + (size_t)b * N * r;
 
     for (int e = tid; e < D * RP; e += kAttnThreads) {
@@ -65,9 +64,9 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
     __syncthreads();
 
     // ---- prologue: Qt^T = V^T Q^T, scaled by scale*log2(e) -------------------------
-    v4f qt[kQB][RB];
+    v4f qt[QB][RB];
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
         for (int ib = 0; ib < RB; ++ib) qt[qb][ib] = v4f{0.f, 0.f, 0.f, 0.f};
         const int m = m_wave + 16 * qb + i16;
@@ -95,10 +94,10 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
     }
 
     // ---- main loop over tiles of P -------------------------------------------------
-    v4f z[kQB][RB];
-    float mrun[kQB], lrun[kQB];
+    v4f z[QB][RB];
+    float mrun[QB], lrun[QB];
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         mrun[qb] = -INFINITY;
         lrun[qb] = 0.f;
 #pragma unroll
@@ -134,11 +133,11 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
         const int n0 = tile * kNT;
 
         // scores S^T[n][m] for the 4 blocks of 16 rows
-        v4f s[kQB][kNT / 16];
+        v4f s[QB][kNT / 16];
 #pragma unroll
         for (int nb = 0; nb < kNT / 16; ++nb) {
 #pragma unroll
-            for (int qb = 0; qb < kQB; ++qb) s[qb][nb] = v4f{0.f, 0.f, 0.f, 0.f};
+            for (int qb = 0; qb < QB; ++qb) s[qb][nb] = v4f{0.f, 0.f, 0.f, 0.f};
             const float* prow = pt + (16 * nb + i16) * LDP;
 #pragma unroll
             for (int ib = 0; ib < RB; ++ib)
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
                 for (int t = 0; t < 4; ++t) {
                     const float a = prow[16 * ib + 4 * t + g];
 #pragma unroll
-                    for (int qb = 0; qb < kQB; ++qb)
+                    for (int qb = 0; qb < QB; ++qb)
                         s[qb][nb] = mfma16x16x4(a, qt[qb][ib][t], s[qb][nb]);
                 }
         }
@@ -158,12 +157,12 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
                 for (int t = 0; t < 4; ++t)
                     if (n0 + 16 * nb + 4 * g + t >= len) {
 #pragma unroll
-                        for (int qb = 0; qb < kQB; ++qb) s[qb][nb][t] = -INFINITY;
+                        for (int qb = 0; qb < QB; ++qb) s[qb][nb][t] = -INFINITY;
                     }
         }
         // online softmax per query (= per lane column), weights overwrite the scores
 #pragma unroll
-        for (int qb = 0; qb < kQB; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
             float mt = -INFINITY;
 #pragma unroll
             for (int nb = 0; nb < kNT / 16; ++nb)
@@ -197,7 +196,7 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
                 for (int ib = 0; ib < RB; ++ib) {
                     const float a = prow[16 * ib + rank_perm(i16)];
 #pragma unroll
-                    for (int qb = 0; qb < kQB; ++qb)
+                    for (int qb = 0; qb < QB; ++qb)
                         z[qb][ib] = mfma16x16x4(a, s[qb][nb][t], z[qb][ib]);
                 }
             }
@@ -206,7 +205,7 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
 
     // ---- epilogue: O^T = V (Z / l)^T ------------------------------------------------
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         float l = lrun[qb];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
@@ -286,27 +285,38 @@ __global__ __launch_bounds__(256) void attention_tokens_kernel(
 
 }  // namespace
 
-template <int D, int RB>
-static hipError_t launch_seq_t(const void* Q, const float* V, const float* P,
+template <int D, int RB, int QB>
+static hipError_t launch_seq_q(const void* Q, const float* V, const float* P,
                                const int32_t* lengths, int B, int N, int r, int M, float scale,
                                bool bf16, float* O, hipStream_t stream) {
     constexpr int RP = 16 * RB;
     const size_t lds = sizeof(float) * ((size_t)D * (RP + 4) + 2 * kNT * (RP + 4));
-    dim3 grid(ceil_div(M, 4 * kQB * 16) * 8 * ceil_div(B, 8)), block(kAttnThreads);
+    dim3 grid(ceil_div(M, 4 * QB * 16) * 8 * ceil_div(B, 8)), block(kAttnThreads);
     if (bf16) {
-        auto kern = attention_seq_kernel<D, RB, true>;
+        auto kern = attention_seq_kernel<D, RB, true, QB>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
     } else {
-        auto kern = attention_seq_kernel<D, RB, false>;
+        auto kern = attention_seq_kernel<D, RB, false, QB>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
     }
     return hipGetLastError();
+}
+
+// A wave takes two 16-query blocks (each row of P read from LDS serves both) unless that leaves
+// fewer workgroups than compute units; then one block per wave fills the GPU.
+template <int D, int RB>
+static hipError_t launch_seq_t(const void* Q, const float* V, const float* P,
+                               const int32_t* lengths, int B, int N, int r, int M, float scale,
+                               bool bf16, float* O, hipStream_t stream) {
+    if ((long long)B * ceil_div(M, 128) < 256)
+        return launch_seq_q<D, RB, 1>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+    return launch_seq_q<D, RB, 2>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
 }
 
 template <int D>
