@@ -195,7 +195,9 @@ __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
 // projects the panel, column after column, out of the later columns it owns.  The order of
 // the projections is that of column-by-column Gram-Schmidt; a panel costs one barrier where
 // that costs kPanel.  Columns that collapse below dead2 (squared norm) are dropped (zero in Qc).
-// The basis is orthonormal to about 2^-24 * cond(Z), which is all a power step needs.
+// The basis is orthonormal to about 2^-24 * cond(Z), which is all a power step needs.  pivot2[j]
+// receives the squared norm column j had when it was normalized (the squared diagonal of the
+// triangular factor, which tends to the eigenvalues of G in decreasing order).
 constexpr int kPanel = 4;
 
 template <int CH>
@@ -207,7 +209,7 @@ __device__ __forceinline__ float dot_ch(const v4f* a, const v4f* b) {
 }
 
 template <int D, int L>
-__device__ __forceinline__ void mgs_orthonormalize(float* Zc, float* Qc, float dead2) {
+__device__ __forceinline__ void mgs_orthonormalize(float* Zc, float* Qc, float* pivot2, float dead2) {
     static_assert(L % kPanel == 0, "the block is a whole number of panels");
     constexpr int LD = D + 4;
     constexpr int TM = min_c(16, D / 4);         // lanes per column
@@ -248,6 +250,7 @@ __device__ __forceinline__ void mgs_orthonormalize(float* Zc, float* Qc, float d
             for (int i = 0; i < kPanel; ++i) {
                 if (team == i) {
                     const float sc = nrm[i] > dead2 ? __builtin_amdgcn_rsqf(nrm[i]) : 0.f;
+                    if (u == 0) pivot2[p0 + i] = nrm[i];   // squared diagonal of the triangular factor
                     float* qi = Qc + (p0 + i) * LD + 4 * u;
 #pragma unroll
                     for (int k = 0; k < CH; ++k) *reinterpret_cast<v4f*>(qi + 4 * TM * k) = a[i][k] * sc;
@@ -288,6 +291,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     float* Gs = resid + 2 * LP + 8;                               // [D][GS] when C::GLDS
     __shared__ int sh_bits;
     __shared__ int sh_bits2;
+    __shared__ float sh_rate[2];
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const float* Gb = G + (size_t)b * D * D;
@@ -436,12 +440,40 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
             --cheap_left;
             have_ritz = false;
             t0 = clock64();
-            mgs_orthonormalize<D, L>(Zc, Qc, dead2);
+            mgs_orthonormalize<D, L>(Zc, Qc, resid, dead2);
             cyc_mgs += clock64() - t0;
+            if (cycle == 0 && cheap_left == 0 && it > 0) {   // the last of the initial cheap steps
+                // Convergence rate seen by this pass: the smallest diagonal entry of the triangular
+                // factor over the r-th largest estimates lambda_(L+1) / lambda_r.  A slowly decaying
+                // spectrum (ratio above 0.3) would fail the check after the usual two steps and pay
+                // a whole Jacobi phase for it, so cheap steps are added up front instead (each costs
+                // a sixth to a tenth of that phase).  (Ending the cheap steps after one when the
+                // ratio is ~ 0, as for inputs of rank r, was tried: one user in eight then failed
+                // the check by a small margin and took seven steps.)
+                if (tid < L) {
+                    const float v = resid[tid];
+                    int rk = 0;
+#pragma unroll 8
+                    for (int k = 0; k < L; ++k) {
+                        const float vk = resid[k];
+                        rk += (vk > v || (vk == v && k < tid)) ? 1 : 0;
+                    }
+                    if (rk == r - 1) sh_rate[0] = v;
+                    if (rk == L - 1) sh_rate[1] = v;
+                }
+                __syncthreads();
+                const float vr = sh_rate[0], vmin = sh_rate[1];
+                const float rho = vr > 0.f ? sqrtf(fmaxf(vmin, 0.f) / vr) : 0.f;
+                if (rho > 0.3f && rho < 1.f) {
+                    const int want = (int)ceilf(-11.5f / __logf(rho)) - 3;   // ln(1e-5) = -11.5
+                    cheap_left = want < 0 ? 0 : (want > 5 ? 5 : want);
+                    cycle = -1;   // the rate is not looked at again
+                }
+            }
             continue;
         }
         // a failed check means slow convergence: spend more cheap steps before the next one
-        ++cycle;
+        cycle = cycle < 0 ? 1 : cycle + 1;
         cheap_left = prm.mgs_steps << (cycle < 3 ? cycle : 3);
         have_ritz = true;
         // orthogonalize the columns of Z (this also rotates them towards Ritz vectors)
