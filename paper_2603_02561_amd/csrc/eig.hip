@@ -89,7 +89,7 @@ __device__ __forceinline__ float team_sum(float v) {
     return v;
 }
 
-// Z = G Q with the float 16x16x4 MFMA, 16x16 output blocks dealt round-robin to the
+// Z = G Q with the float 16x16x4 MFMA, block rows of 16 dealt round-robin to the
 // waves.  G is symmetric, so A[i][k] = G[k][i] is read with the 16 lanes of a slot group
 // on consecutive addresses.  Q and Z are stored column by column (column j at j*LD).
 // Gb has row stride GS: the copy of G in LDS (row stride D + 16, which puts the two slot
@@ -97,17 +97,26 @@ __device__ __forceinline__ float team_sum(float v) {
 template <int D, int LP, int GS>
 __device__ __forceinline__ void gemm_gq(const float* Gb, const float* Qc, float* Zc) {
     constexpr int LD = D + 4;
-    constexpr int NRB = D / 16, NB = NRB * (LP / 16);
+    constexpr int NRB = D / 16, NCB = LP / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i16 = lane & 15, g = lane >> 4;
-    for (int blk = wave; blk < NB; blk += kEigWaves) {
-        const int ib = blk % NRB, cb = blk / NRB;
+    // a wave takes whole block rows: the operand read from G serves all NCB column blocks, whose
+    // accumulators are independent chains for the matrix unit
+    for (int ib = wave; ib < NRB; ib += kEigWaves) {
         const float* ga = Gb + g * GS + 16 * ib + i16;
-        const float* qb = Qc + (16 * cb + i16) * LD + g;
-        v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 16
-        for (int k0 = 0; k0 < D; k0 += 4) acc = mfma16x16x4(ga[k0 * GS], qb[k0], acc);
-        *reinterpret_cast<v4f*>(&Zc[(16 * cb + i16) * LD + 16 * ib + 4 * g]) = acc;
+        const float* qb = Qc + i16 * LD + g;
+        v4f acc[NCB];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) acc[cb] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+        for (int k0 = 0; k0 < D; k0 += 4) {
+            const float a = ga[k0 * GS];
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) acc[cb] = mfma16x16x4(a, qb[16 * cb * LD + k0], acc[cb]);
+        }
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+            *reinterpret_cast<v4f*>(&Zc[(16 * cb + i16) * LD + 16 * ib + 4 * g]) = acc[cb];
     }
 }
 
