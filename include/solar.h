@@ -87,7 +87,8 @@ size_t solar_workspace_bytes(int B, int N, int d, int r, int M, solar_dtype t);
  *                        through a float Gram matrix: they come back as S = 0 with
  *                        a zero column of V.
  *   P        out [B,N,r] = X V, rows at or past the valid length are zero; may be
- *                        NULL if only modes 1 and 2 will be used
+ *                        NULL if only modes 1 and 2 or solar_svd_attention_from_x
+ *                        will be used
  *   info     out [B] or NULL: 0 converged; k > 0 iteration cap reached after k
  *                        steps (results are the best available); -1 bad length
  *                        (not in [r, N]; that user's outputs are zero)
