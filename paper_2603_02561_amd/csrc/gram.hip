@@ -358,6 +358,196 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram256_partial_kernel(
     reduce_waves_and_store<NP>(acc, out);
 }
 
+// bf16 inputs: the four jobs are the four waves of one workgroup and share every row block through
+// LDS, so X is read from HBM once.  Wave w loads columns 64w .. 64w+63 of a 32-row block (16 lanes
+// per row, four columns per lane), transposes them in registers into the four MFMA operand
+// fragments 4w .. 4w+3 (fragment f, lane j: column 64 (f/4) + 4j + f%4) and parks them in LDS; after
+// one barrier every wave reads the 8 or 12 fragments of its job.  Fragments 0..7 are the left half
+// X0, 8..15 the right half X1, so the jobs and the partial slots are those of the layout above.
+// The fragment buffer is double: a wave that writes block i+2 has passed the barrier of block
+// i+1, which every wave reaches only after its reads of block i.  Loads run kGram256Ring - 1
+// blocks ahead in registers (16 registers per block and lane), unconditional and clamped to the
+// chunk's last row as in gram_partial_kernel.
+constexpr int kGram256Ring = 4;
+
+__global__ __launch_bounds__(kGramWaves * 64) void gram256_shared_kernel(
+    const void* __restrict__ Xv, const int32_t* __restrict__ lengths, int N, int nsplit,
+    float* __restrict__ partials) {
+    constexpr int D = 256, NP = kGram256Pairs, STEP = 32, kRing = kGram256Ring;
+    static_assert(kRing % 2 == 0, "the LDS buffer index follows the ring slot's parity");
+    __shared__ __attribute__((aligned(16))) v4u fragbuf[2][16][64];
+    const int b = blockIdx.y, split = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j = lane & 15, h = lane >> 4;
+    const int len = user_len(lengths, b, N);
+    const int chunk = ceil_div(ceil_div(len, nsplit), STEP) * STEP;
+    const int r0 = split * chunk;
+    const int r1 = min(len, r0 + chunk);
+    const int nblk = r1 > r0 ? ceil_div(r1 - r0, STEP) : 0;   // the same for all four waves
+    const int nwhole = r1 > r0 ? (r1 - r0) / STEP : 0;
+    const int row_max = max(r1 - 1, 0);
+    const uint32_t* X = reinterpret_cast<const uint32_t*>(Xv) + (size_t)b * N * (D / 2) + 32 * wave + 2 * j;
+
+    v4f acc[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) acc[p] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    auto load = [&](uint2 (&dst)[8], int blk) __attribute__((always_inline)) {
+        const int base = r0 + blk * STEP + 8 * h;
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            dst[t] = *reinterpret_cast<const uint2*>(X + (size_t)min(base + t, row_max) * (D / 2));
+    };
+    auto stage = [&](const uint2 (&src)[8], int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            uint32_t o[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t lo = (s / 2) ? src[2 * u].y : src[2 * u].x;
+                const uint32_t hi = (s / 2) ? src[2 * u + 1].y : src[2 * u + 1].x;
+                o[u] = __builtin_amdgcn_perm(hi, lo, (s & 1) ? 0x07060302u : 0x05040100u);
+            }
+            fragbuf[buf][4 * wave + s][lane] = v4u{o[0], o[1], o[2], o[3]};
+        }
+    };
+    auto stage_tail = [&](uint2 (&src)[8], int blk, int buf) __attribute__((always_inline)) {
+        const int base = r0 + blk * STEP + 8 * h;
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            if (base + t >= r1) src[t] = uint2{0u, 0u};
+        stage(src, buf);
+    };
+    auto consume = [&](int buf) __attribute__((always_inline)) {
+        if (wave < 2) {
+            v4u f[8];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) f[s] = fragbuf[buf][8 * wave + s][lane];
+            int p = 0;
+#pragma unroll
+            for (int s1 = 0; s1 < 8; ++s1)
+#pragma unroll
+                for (int s2 = s1; s2 < 8; ++s2) {
+                    acc[p] = mfma16x16x32bf16(f[s1], f[s2], acc[p]);
+                    ++p;
+                }
+        } else {
+            v4u fa[4], fb[8];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) fa[s] = fragbuf[buf][4 * (wave - 2) + s][lane];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) fb[s] = fragbuf[buf][8 + s][lane];
+#pragma unroll
+            for (int s1 = 0; s1 < 4; ++s1)
+#pragma unroll
+                for (int s2 = 0; s2 < 8; ++s2)
+                    acc[s1 * 8 + s2] = mfma16x16x32bf16(fa[s1], fb[s2], acc[s1 * 8 + s2]);
+        }
+    };
+
+    uint2 ring[kRing][8];
+#pragma unroll
+    for (int k = 0; k < kRing - 1; ++k) load(ring[k], k);
+    int i = 0;
+    for (; i + kRing <= nwhole; i += kRing) {
+#pragma unroll
+        for (int k = 0; k < kRing; ++k) {
+            load(ring[(k + kRing - 1) % kRing], i + k + kRing - 1);
+            __builtin_amdgcn_sched_barrier(0);   // the prefetch is issued before the block is used
+            stage(ring[k], k & 1);
+            __syncthreads();
+            consume(k & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kRing; ++k) {
+        if (i + k < nblk) {
+            if (i + k + kRing - 1 < nblk) load(ring[(k + kRing - 1) % kRing], i + k + kRing - 1);
+            stage_tail(ring[k], i + k, k & 1);
+            __syncthreads();
+            consume(k & 1);
+        }
+    }
+
+    v4f* out = reinterpret_cast<v4f*>(partials) + (((size_t)b * nsplit + split) * 4 + wave) * (NP * 64);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) out[p * 64 + lane] = acc[p];
+}
+
+// Sum over the chunks and undo the fragment permutation of gram256_shared_kernel.  A workgroup
+// owns one 64 x 64 block (q1 <= q2) of G's 4 x 4 block form, i.e. the 4 x 4 fragment pairs
+// (4 q1 + s1, 4 q2 + s2): wave s1 reads the partial blocks of its four pairs as they were stored
+// (one 16-byte element per lane and chunk, consecutive lanes consecutive addresses), adds the
+// chunks in a fixed order, and drops the sums into an LDS tile at (4 i1 + s1, 4 i2 + s2); the tile
+// then goes out row by row, and transposed into the mirror block when q1 < q2.  On the diagonal
+// only the pairs s1 <= s2 exist; their mirror images fill the rest of the tile.
+__global__ __launch_bounds__(256) void gram256_gather_kernel(const float* __restrict__ partials, int nsplit,
+                                                             float* __restrict__ G) {
+    constexpr int D = 256, NP = kGram256Pairs, T = 64, LDT = T + 1;
+    __shared__ float tile[T * LDT];
+    const int b = blockIdx.y;
+    int q1 = 0, q2 = blockIdx.x;                       // blockIdx.x enumerates the pairs q1 <= q2
+    while (q2 >= 4 - q1) { q2 -= 4 - q1; ++q1; }
+    q2 += q1;
+    const int lane = threadIdx.x & 63, s1 = threadIdx.x >> 6;
+    const bool diag = q1 == q2;
+    const bool same_half = q1 / 2 == q2 / 2;
+    const int fl1 = 4 * (q1 % 2) + s1;
+    const int job = same_half ? q1 / 2 : 2 + q1 % 2;
+    const v4f* base = reinterpret_cast<const v4f*>(partials) + ((size_t)b * nsplit * 4 + job) * (NP * 64) + lane;
+    const size_t split_stride = (size_t)4 * NP * 64;
+    v4f sum[4];
+    int pair[4];
+    const int row_start = fl1 * 8 - (fl1 * (fl1 - 1)) / 2;   // slot of the pair (fl1, fl1)
+#pragma unroll
+    for (int s2 = 0; s2 < 4; ++s2) {
+        const int fl2 = 4 * (q2 % 2) + s2;
+        // a pair below the diagonal is not stored: it reads the slot (fl1, fl1) and drops the value
+        pair[s2] = same_half ? row_start + max(fl2 - fl1, 0) : s1 * 8 + fl2;
+        sum[s2] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
+    // four chunks (16 loads) are in flight before the first is added; the order of the additions is
+    // that of the chunks either way
+    int s = 0;
+    for (; s + 4 <= nsplit; s += 4) {
+        v4f part[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) part[u][s2] = base[(size_t)(s + u) * split_stride + pair[s2] * 64];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) sum[s2] += part[u][s2];
+    }
+    for (; s < nsplit; ++s) {
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) sum[s2] += base[(size_t)s * split_stride + pair[s2] * 64];
+    }
+    const int i2 = lane & 15;
+#pragma unroll
+    for (int s2 = 0; s2 < 4; ++s2) {
+        if (diag && s2 < s1) continue;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int i1 = 4 * (lane >> 4) + k;
+            const int row = 4 * i1 + s1, col = 4 * i2 + s2;
+            tile[row * LDT + col] = sum[s2][k];
+            if (diag && s2 > s1) tile[col * LDT + row] = sum[s2][k];
+        }
+    }
+    __syncthreads();
+    float* Gb = G + (size_t)b * D * D;
+    for (int e = threadIdx.x; e < T * T; e += 256) {
+        const int row = e / T, col = e % T;
+        Gb[(size_t)(T * q1 + row) * D + T * q2 + col] = tile[row * LDT + col];
+        if (!diag) Gb[(size_t)(T * q2 + row) * D + T * q1 + col] = tile[col * LDT + row];
+    }
+}
+
 __global__ __launch_bounds__(256) void gram256_finalize_kernel(const float* __restrict__ partials,
                                                                int nsplit, float* __restrict__ G) {
     constexpr int D = 256, CPL = 8, NP = kGram256Pairs;
@@ -443,7 +633,15 @@ hipError_t launch_gram(const void* X, const int32_t* lengths, int B, int N, int 
         case 128: return launch_gram_t<8>(X, lengths, B, N, bf16, partials, G, finalize, stream);
         case 256: {
             const int nsplit = gram_nsplit(B, N);
-            dim3 grid(nsplit, B, 4), block(kGramWaves * 64);
+            dim3 block(kGramWaves * 64), g2(256 * 256 / 256, B);
+            static const bool separate_jobs = std::getenv("SOLAR_GRAM256_JOBS") != nullptr;   // tuning aid
+            if (bf16 && !separate_jobs) {
+                hipLaunchKernelGGL(gram256_shared_kernel, dim3(nsplit, B), block, 0, stream, X, lengths, N, nsplit,
+                                   partials);
+                hipLaunchKernelGGL(gram256_gather_kernel, dim3(10, B), dim3(256), 0, stream, partials, nsplit, G);
+                return hipGetLastError();
+            }
+            dim3 grid(nsplit, B, 4);
             constexpr size_t lds = gram_reduce_lds<kGram256Pairs>();
             hipError_t e = bf16 ? gram_allow_lds(gram256_partial_kernel<true>, lds)
                                 : gram_allow_lds(gram256_partial_kernel<false>, lds);
@@ -454,8 +652,7 @@ hipError_t launch_gram(const void* X, const int32_t* lengths, int B, int N, int 
             else
                 hipLaunchKernelGGL((gram256_partial_kernel<false>), grid, block, lds, stream, X, lengths, N,
                                    nsplit, partials);
-            hipLaunchKernelGGL(gram256_finalize_kernel, dim3(256 * 256 / 256, B), dim3(256), 0, stream,
-                               partials, nsplit, G);
+            hipLaunchKernelGGL(gram256_finalize_kernel, g2, dim3(256), 0, stream, partials, nsplit, G);
             return hipGetLastError();
         }
         default: return hipErrorInvalidValue;

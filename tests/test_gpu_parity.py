@@ -87,6 +87,33 @@ def test_gram(lib, oracle, name, w):
     assert torch.equal(G, G2)
 
 
+def test_gram_d256_bf16_ragged_lengths(lib, oracle):
+    """d = 256 with bf16 inputs takes the Gram kernel whose four waves share each 32-row block
+    through LDS.  Lengths around its block (32 rows), its unrolled loop (4 blocks) and the split of
+    the sequence into chunks: a single row, one block exactly, one row more, a chunk that ends up
+    empty, a whole number of loop trips, and the full length.  The matrix has no structure, so a
+    misplaced fragment shows in every entry."""
+    import torch
+    B, N, d = 8, 1300, 256
+    lengths = np.asarray([1, 32, 33, 127, 128, 129, 1025, 1300], dtype=np.int32)
+    rng = np.random.default_rng(4256)
+    X = synth.round_to_bf16(rng.standard_normal((B, N, d)).astype(np.float32))
+    Q = synth.round_to_bf16(rng.standard_normal((B, 4, d)).astype(np.float32))
+    db = lib.DeviceBatch(X, Q, lengths, 8, True)
+    G = torch.empty((B, d, d), dtype=torch.float32, device="cuda")
+    print(f"[case] gram d256 bf16 ragged lengths {lengths.tolist()}", flush=True)
+    lib.solar_gram(db.X, db.lengths, G, db.workspace)
+    torch.cuda.synchronize()
+    want = oracle.gram(X, lengths)
+    err = rel_err(G.cpu().numpy(), want)
+    print(f"  gram err {err:.3e}", flush=True)
+    assert err < 2e-6
+    G2 = torch.empty_like(G)
+    lib.solar_gram(db.X, db.lengths, G2, db.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(G, G2)
+
+
 @pytest.mark.parametrize("name,w", WORKLOADS, ids=IDS)
 def test_dense_reference(lib, oracle, name, w):
     import torch
