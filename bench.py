@@ -259,9 +259,10 @@ def main() -> int:
         "attention": ("mfma", float(np.sum(4.0 * w.M * lens * w.r) + w.B * 4.0 * w.M * w.r * w.d)),
     }
     mfma_peak = PEAKS["mfma_bf16_TFLOPs"] if bf16 else PEAKS["mfma_f32_TFLOPs"]
-    kernel_names = {"gram": "gram_partial_kernel", "eig": "eig_topr_kernel",
+    kernel_names = {"gram": "gram256_shared_kernel" if (bf16 and w.d == 256) else "gram_partial_kernel",
+                    "eig": "eig_topr_kernel",
                     "project": "project_bf16_kernel" if bf16 else "project_kernel",
-                    "attention": ("attention_seq_x32_kernel" if w.r <= 32 else "attention_seq_bf16_kernel")
+                    "attention": ("attention_seq_x32_kernel" if (w.r <= 64 and w.r % 4 == 0) else "attention_seq_bf16_kernel")
                     if bf16 else "attention_seq_kernel"}
     phases = {"gram": gram_ms, "eig": eig_ms, "project": proj_ms, "attention": attn_ms}
     kernels = {}

@@ -285,7 +285,7 @@ solar_status solar_svd_attention_from_x(const void* Q, const void* X, const floa
     if (!Q || !X || !S || !V || !O || B <= 0 || N <= 0 || d <= 0 || r <= 0 || M <= 0) return SOLAR_ERR_INVALID_ARG;
     if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
     if (r > d) return SOLAR_ERR_INVALID_ARG;
-    if (t != SOLAR_BF16 || !attention_seq_x32_supported(d, r)) return SOLAR_ERR_UNSUPPORTED;
+    if (t != SOLAR_BF16 || !attention_seq_x32_from_x_supported(d, r)) return SOLAR_ERR_UNSUPPORTED;
     hipError_t e = launch_attention_seq_x32_from_x(Q, S, V, X, lengths, B, N, d, r, M, scale, O, (hipStream_t)stream);
     return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
 }

@@ -1,6 +1,8 @@
 // SVD-Attention in its sequence-softmax form, O = softmax_n(scale * Qt P^T) P V^T
-// (Section "SVD-Attention"; Qt = Q V, P = X V), fast path for bf16 inputs and rank <= 32
-// on the 32x32x16 fp16 matrix instruction of gfx950.
+// (Section "SVD-Attention"; Qt = Q V, P = X V), fast path for bf16 inputs and rank <= 64
+// on the 32x32x16 fp16 matrix instruction of gfx950.  The rank is padded to RP = 32 (one
+// 32-rank half; what follows describes it) or RP = 64 (two halves: twice the score and Z
+// products per block, which loads the matrix unit as heavily as the vector ALU's issue port).
 //
 // The kernel is bound by the issue port of the vector ALU, which the matrix instructions
 // share.  Measured per wave instruction: an MFMA holds the port for about 8 cycles whatever
@@ -55,10 +57,8 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kQW = 32;              // queries per wave
 constexpr int kNT = 128;             // rows of P per tile
 constexpr int kNB = kNT / 32;        // blocks per tile
-constexpr int RP = 32;               // padded rank
-constexpr int LDV = RP + 1;          // floats, V image [D][LDV]
-constexpr int LDR = RP + 8;          // fp16 elements, tile image [kNT][LDR]
-constexpr int kBuf = kNT * LDR;      // elements of one tile buffer
+// RP is the padded rank (32 or 64): LDV = RP + 1 floats per row of the V image [D][LDV],
+// LDR = RP + 8 fp16 elements per row of a tile image [kNT][LDR]
 constexpr float kLog2e = 1.4426950408889634f;
 // a score more than kShift (in log2 units) above the reference moves the reference there, so
 // no weight exceeds 2^kShift: far inside the fp16 range, and the row sums stay far inside float
@@ -112,11 +112,16 @@ __device__ __forceinline__ int quad_pos(int c4) { return (c4 & ~3) | ((c4 & 1) <
 // FUSED: Pin is the user's X (bf16, [B][N][D]) and the loader forms the rows of P = X V itself
 // (the projection of Section "SVD-Attention" evaluated where it is consumed; every workgroup of
 // a user repeats it); otherwise Pin is P (float, [B][N][r]).
-template <int D, bool FUSED>
+template <int D, int RP, bool FUSED>
 __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const void* __restrict__ Qv, const float* __restrict__ S, const float* __restrict__ V,
     const void* __restrict__ Pin, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
     float scale, int guarded_only, float* __restrict__ O) {
+    static_assert(RP == 32 || RP == 64, "one or two 32-rank halves");
+    static_assert(!FUSED || RP == 32, "the fused loader is written for one rank half");
+    constexpr int LDV = RP + 1, LDR = RP + 8, kBuf = kNT * LDR;
+    constexpr int NC = RP / 16;   // 16-rank chunks of the score product
+    constexpr int NH = RP / 32;   // 32-rank halves of Z
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                                              // [D][LDV]
     uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);   // [3][kBuf]
@@ -166,11 +171,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 
     // ---- prologue: Qt^T = V^T Q^T in float (32x32x2 MFMA; the contraction slot of lane half
     // h in step s is coordinate (D/2)*h + s), scaled by scale*log2(e), rounded to fp16 -------
-    v4u qB[2];
+    v4u qB[NC];
     {
-        v16f qt;
+        v16f qt[NH];
 #pragma unroll
-        for (int t = 0; t < 16; ++t) qt[t] = 0.f;
+        for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+            for (int t = 0; t < 16; ++t) qt[hh][t] = 0.f;
         const int m = m_wave + n32;
         const bool valid = m < M;
         const uint16_t* qrow = reinterpret_cast<const uint16_t*>(Qv) + ((size_t)b * M + (valid ? m : 0)) * D +
@@ -181,34 +188,41 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             if (!valid) w = v4u{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                qt = __builtin_amdgcn_mfma_f32_32x32x2f32(vcol[(8 * cc + 2 * e) * LDV], bf16_lo(w[e]), qt, 0, 0, 0);
-                qt = __builtin_amdgcn_mfma_f32_32x32x2f32(vcol[(8 * cc + 2 * e + 1) * LDV], bf16_hi(w[e]), qt, 0, 0, 0);
+#pragma unroll
+                for (int hh = 0; hh < NH; ++hh) {
+                    qt[hh] = __builtin_amdgcn_mfma_f32_32x32x2f32(vcol[(8 * cc + 2 * e) * LDV + 32 * hh], bf16_lo(w[e]),
+                                                                  qt[hh], 0, 0, 0);
+                    qt[hh] = __builtin_amdgcn_mfma_f32_32x32x2f32(vcol[(8 * cc + 2 * e + 1) * LDV + 32 * hh],
+                                                                  bf16_hi(w[e]), qt[hh], 0, 0, 0);
+                }
             }
         }
-        // B operand of the score product, chunk c: slot u of lane half h is register 8*c + u
+        // B operand of the score product, chunk c: slot u of lane half h is register 8*(c%2) + u of
+        // rank half c/2
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
+        for (int c = 0; c < NC; ++c) {
             float q[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                q[u] = fminf(fmaxf(qt[8 * c + u] * (scale * kLog2e * punscale), -6.0e4f), 6.0e4f);
+                q[u] = fminf(fmaxf(qt[c / 2][8 * (c % 2) + u] * (scale * kLog2e * punscale), -6.0e4f), 6.0e4f);
             qB[c] = v4u{pack_f16(q[0], q[1]), pack_f16(q[2], q[3]), pack_f16(q[4], q[5]), pack_f16(q[6], q[7])};
         }
     }
 
     // ---- tile loader: float P -> fp16 image [kNT][LDR] ------------------------------------
-    // A thread owns two consecutive rows and four consecutive ranks of a tile.  The loads carry
+    // A thread owns RPT consecutive rows and four consecutive ranks of a tile.  The loads carry
     // no predicate: byte offsets into the user's P advance by one tile per fetch, and for a
     // ragged last tile the rows are clamped to the last valid one (they are zeroed when that
     // tile is converted).  Rank quads at or beyond r load quad r/4-1 and are never stored.
     constexpr int kQuads = RP / 4;
-    static_assert((kNT / 2) * kQuads == kThreads, "one loader task per thread");
+    constexpr int RPT = kNT * kQuads / kThreads;   // rows per thread: 2 or 4
+    static_assert((kNT / RPT) * kQuads == kThreads, "one loader task per thread");
     const int nfull = len / kNT;   // tiles whose rows are all valid
     const int last_row = max(len - 1, 0);   // clamp of the row index of loads past the valid length
-    // -- P given: a thread owns two consecutive rows and four consecutive ranks of a tile
+    // -- P given: a thread owns RPT consecutive rows and four consecutive ranks of a tile
     const int ld_np = tid / kQuads, ld_c4 = tid % kQuads;
     const bool ld_active = 4 * ld_c4 < r;
-    const int ld_dst = (2 * ld_np) * LDR + 4 * quad_pos(ld_c4);
+    const int ld_dst = (RPT * ld_np) * LDR + 4 * quad_pos(ld_c4);
     const uint32_t row_bytes = FUSED ? 2u * D : 4u * (uint32_t)r;
     const uint32_t ld_col = 16u * (uint32_t)min(ld_c4, (r >> 2) - 1);
     // -- X given: wave w owns rows 16*w .. 16*w+15 of a tile; lane (row l%16, group l/16) loads
@@ -219,11 +233,11 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const int fx_row = 16 * wave + (lane & 15), fx_g = lane >> 4;
     const char* Pbytes = reinterpret_cast<const char*>(Pin) +
                          (FUSED ? (size_t)b * N * (2u * D) + (size_t)fx_g * (D / 2) : (size_t)b * N * (4u * r));
-    const uint32_t ld_off0 = FUSED ? (uint32_t)fx_row * row_bytes : (uint32_t)(2 * ld_np) * row_bytes + ld_col;
+    const uint32_t ld_off0 = FUSED ? (uint32_t)fx_row * row_bytes : (uint32_t)(RPT * ld_np) * row_bytes + ld_col;
     uint32_t ld_off = ld_off0;   // this thread's first row of the next tile to fetch
     // two sets of staging registers: a tile is loaded two loop iterations before it is converted,
     // so that the loads (L2 or HBM) have a whole tile of arithmetic to arrive
-    v4f stage[2][2];
+    v4f stage[2][RPT];
     v4u xst[2][FUSED ? KS : 1];
     auto fetch = [&](int tile, auto par_tag) __attribute__((always_inline)) {
         constexpr int par = decltype(par_tag)::value;
@@ -235,14 +249,16 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) xst[par][ks] = p[ks];
         } else {
-            uint32_t o0 = ld_off, o1 = ld_off + row_bytes;
+            uint32_t o[RPT];
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) o[i] = ld_off + i * row_bytes;
             if (__builtin_expect(tile >= nfull, 0)) {   // uniform: the ragged last tile
-                const int n0 = min(tile * kNT + 2 * ld_np, last_row), n1 = min(tile * kNT + 2 * ld_np + 1, last_row);
-                o0 = (uint32_t)n0 * row_bytes + ld_col;
-                o1 = (uint32_t)n1 * row_bytes + ld_col;
+#pragma unroll
+                for (int i = 0; i < RPT; ++i)
+                    o[i] = (uint32_t)min(tile * kNT + RPT * ld_np + i, last_row) * row_bytes + ld_col;
             }
-            stage[par][0] = *reinterpret_cast<const v4f*>(Pbytes + o0);
-            stage[par][1] = *reinterpret_cast<const v4f*>(Pbytes + o1);
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) stage[par][i] = *reinterpret_cast<const v4f*>(Pbytes + o[i]);
         }
         ld_off += (uint32_t)kNT * row_bytes;
     };
@@ -270,15 +286,16 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
                         uint2{pack_f16(pa[0], pa[1]), pack_f16(pa[2], pa[3])};
             }
         } else if (ld_active) {
-            v4f x0 = stage[par][0], x1 = stage[par][1];
-            if (__builtin_expect(tile >= nfull, 0)) {   // uniform
-                if (tile * kNT + 2 * ld_np >= len) x0 = v4f{0.f, 0.f, 0.f, 0.f};
-                if (tile * kNT + 2 * ld_np + 1 >= len) x1 = v4f{0.f, 0.f, 0.f, 0.f};
-            }
-            if (__builtin_expect(rescale, 0)) { x0 *= pscale; x1 *= pscale; }   // uniform
             uint16_t* dst = buf + ld_dst;
-            *reinterpret_cast<uint2*>(dst) = uint2{pack_f16(x0[0], x0[1]), pack_f16(x0[2], x0[3])};
-            *reinterpret_cast<uint2*>(dst + LDR) = uint2{pack_f16(x1[0], x1[1]), pack_f16(x1[2], x1[3])};
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+                v4f x = stage[par][i];
+                if (__builtin_expect(tile >= nfull, 0)) {   // uniform
+                    if (tile * kNT + RPT * ld_np + i >= len) x = v4f{0.f, 0.f, 0.f, 0.f};
+                }
+                if (__builtin_expect(rescale, 0)) x *= pscale;   // uniform
+                *reinterpret_cast<uint2*>(dst + i * LDR) = uint2{pack_f16(x[0], x[1]), pack_f16(x[2], x[3])};
+            }
         }
     };
 
@@ -289,12 +306,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // G/2; lane i of the group points at row 4*(G/2) + i/4 (+8 for the second read, +16 for
     // the second chunk), rank quad 4*(G%2) + i%4
     const int za_off = (4 * h + ((lane & 15) >> 2)) * LDR + 4 * quad_pos(4 * ((lane >> 4) & 1) + (lane & 3));
-    v4u sA[2][2], zA[2][2];     // [block parity][chunk]
+    v4u sA[2][NC];              // [block parity][rank chunk]
+    v4u zA[2][NH][2];           // [block parity][rank half][row chunk]
 
     // ---- state --------------------------------------------------------------------------------
     v16f s[2];          // scores of two consecutive blocks, relative to mref
     v4u wp[2][2];       // packed weights [block parity][chunk]
-    v16f z;             // Z^T, rank 8*(t/4) + 4*h + t%4 of query n32
+    v16f z[NH];         // Z^T, rank 32*half + 8*(t/4) + 4*h + t%4 of query n32
     v16f cinit;         // -mref in every register: start value of the score accumulators
     v4f lacc;           // row sums of the weights: lanes 0..15 hold query `lane` in component 0 and
                         // query `lane + 16` in component 1 (rows 0 and 1 of a 16x16 product)
@@ -308,12 +326,17 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const v4u ones = v4u{one2, one2, one2, one2};
     auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < 16; ++t) { z[t] = 0.f; cinit[t] = 0.f; }
+        for (int t = 0; t < 16; ++t) {
+            cinit[t] = 0.f;
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) z[hh][t] = 0.f;
+        }
         lacc = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             wp[0][c] = wp[1][c] = v4u{0u, 0u, 0u, 0u};
-            zA[0][c] = zA[1][c] = v4u{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) zA[0][hh][c] = zA[1][hh][c] = v4u{0u, 0u, 0u, 0u};
         }
         mref = 0.f; smax = 0.f;
         ld_off = ld_off0;
@@ -334,7 +357,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
             s[cur][t] -= shift;
-            z[t] *= alpha;
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) z[hh][t] *= alpha;
             cinit[t] = -mref;
         }
 #pragma unroll
@@ -389,70 +413,120 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             if constexpr (guarded) smax = fmaxf(fmaxf(i == 0 ? s[nxt][0] : smax, s[nxt][4 * i + (i == 0 ? 1 : 0)]),
                          fmaxf(s[nxt][4 * i + (i == 0 ? 2 : 1)], fmaxf(s[nxt][4 * i + (i == 0 ? 3 : 2)], s[nxt][4 * i + 3])));
         };
-        SOLAR_FENCE;
-        __builtin_amdgcn_s_setprio(1);
-        s[nxt] = mma32(sA[nxt][0], qB[0], cinit);
-        __builtin_amdgcn_s_setprio(0);
-        SOLAR_FENCE;
-        E(0); sA[cur][0] = *reinterpret_cast<const v4u*>(sa_next);
-        SOLAR_FENCE;
-        E(1); sA[cur][1] = *reinterpret_cast<const v4u*>(sa_next + 16);
-        SOLAR_FENCE;
-        uint2 zlo, zhi;
-        E(2); zlo = lds_read_tr16(za_this);
-        SOLAR_FENCE;
-        E(3); zhi = lds_read_tr16(za_this + 8 * LDR);
-        SOLAR_FENCE;
-        __builtin_amdgcn_s_setprio(1);
-        s[nxt] = mma32(sA[nxt][1], qB[1], s[nxt]);
-        __builtin_amdgcn_s_setprio(0);
-        SOLAR_FENCE;
-        E(4); C(0);
-        SOLAR_FENCE;
-        E(5); C(1);
-        SOLAR_FENCE;
-        E(6);
-        SOLAR_FENCE;
-        E(7);
-        SOLAR_FENCE;
-        __builtin_amdgcn_s_setprio(1);
-        z = mma32(zA[nxt][0], wp[nxt][0], z);
-        __builtin_amdgcn_s_setprio(0);
-        SOLAR_FENCE;
-        zA[cur][0] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
-        E(8); C(2);
-        SOLAR_FENCE;
-        E(9); C(3);
-        SOLAR_FENCE;
-        E(10);
-        SOLAR_FENCE;
-        E(11);
-        SOLAR_FENCE;
-        __builtin_amdgcn_s_setprio(1);
-        z = mma32(zA[nxt][1], wp[nxt][1], z);
-        __builtin_amdgcn_s_setprio(0);
-        SOLAR_FENCE;
-        __builtin_amdgcn_s_setprio(1);
-        lacc = mma16(ones, wp[cur][0], lacc);
-        __builtin_amdgcn_s_setprio(0);
-        SOLAR_FENCE;
-        E(12); zlo = lds_read_tr16(za_this + 16 * LDR);
-        SOLAR_FENCE;
-        E(13); zhi = lds_read_tr16(za_this + 24 * LDR);
-        SOLAR_FENCE;
-        E(14); C(4); X(0);
-        SOLAR_FENCE;
-        E(15); C(5); X(1);
-        SOLAR_FENCE;
-        C(6); C(7);
-        zA[cur][1] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
-        SOLAR_FENCE;
-        __builtin_amdgcn_s_setprio(1);
-        lacc = mma16(ones, wp[cur][1], lacc);
-        __builtin_amdgcn_s_setprio(0);
-        SOLAR_FENCE;
-        X(2); X(3);
-        SOLAR_FENCE;
+        if constexpr (RP == 32) {
+            SOLAR_FENCE;
+            __builtin_amdgcn_s_setprio(1);
+            s[nxt] = mma32(sA[nxt][0], qB[0], cinit);
+            __builtin_amdgcn_s_setprio(0);
+            SOLAR_FENCE;
+            E(0); sA[cur][0] = *reinterpret_cast<const v4u*>(sa_next);
+            SOLAR_FENCE;
+            E(1); sA[cur][1] = *reinterpret_cast<const v4u*>(sa_next + 16);
+            SOLAR_FENCE;
+            uint2 zlo, zhi;
+            E(2); zlo = lds_read_tr16(za_this);
+            SOLAR_FENCE;
+            E(3); zhi = lds_read_tr16(za_this + 8 * LDR);
+            SOLAR_FENCE;
+            __builtin_amdgcn_s_setprio(1);
+            s[nxt] = mma32(sA[nxt][1], qB[1], s[nxt]);
+            __builtin_amdgcn_s_setprio(0);
+            SOLAR_FENCE;
+            E(4); C(0);
+            SOLAR_FENCE;
+            E(5); C(1);
+            SOLAR_FENCE;
+            E(6);
+            SOLAR_FENCE;
+            E(7);
+            SOLAR_FENCE;
+            __builtin_amdgcn_s_setprio(1);
+            z[0] = mma32(zA[nxt][0][0], wp[nxt][0], z[0]);
+            __builtin_amdgcn_s_setprio(0);
+            SOLAR_FENCE;
+            zA[cur][0][0] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
+            E(8); C(2);
+            SOLAR_FENCE;
+            E(9); C(3);
+            SOLAR_FENCE;
+            E(10);
+            SOLAR_FENCE;
+            E(11);
+            SOLAR_FENCE;
+            __builtin_amdgcn_s_setprio(1);
+            z[0] = mma32(zA[nxt][0][1], wp[nxt][1], z[0]);
+            __builtin_amdgcn_s_setprio(0);
+            SOLAR_FENCE;
+            __builtin_amdgcn_s_setprio(1);
+            lacc = mma16(ones, wp[cur][0], lacc);
+            __builtin_amdgcn_s_setprio(0);
+            SOLAR_FENCE;
+            E(12); zlo = lds_read_tr16(za_this + 16 * LDR);
+            SOLAR_FENCE;
+            E(13); zhi = lds_read_tr16(za_this + 24 * LDR);
+            SOLAR_FENCE;
+            E(14); C(4); X(0);
+            SOLAR_FENCE;
+            E(15); C(5); X(1);
+            SOLAR_FENCE;
+            C(6); C(7);
+            zA[cur][0][1] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
+            SOLAR_FENCE;
+            __builtin_amdgcn_s_setprio(1);
+            lacc = mma16(ones, wp[cur][1], lacc);
+            __builtin_amdgcn_s_setprio(0);
+            SOLAR_FENCE;
+            X(2); X(3);
+            SOLAR_FENCE;
+        } else {
+            // two rank halves: four score products and four Z products per block; the matrix unit
+            // is then as busy as the vector ALU's issue port, so its instructions are spread evenly
+#define SOLAR_MFMA(stmt) SOLAR_FENCE; __builtin_amdgcn_s_setprio(1); stmt; __builtin_amdgcn_s_setprio(0); SOLAR_FENCE
+            uint2 t0, t1, t2, t3;
+            SOLAR_MFMA(s[nxt] = mma32(sA[nxt][0], qB[0], cinit));
+            E(0); sA[cur][0] = *reinterpret_cast<const v4u*>(sa_next);
+            SOLAR_FENCE;
+            E(1); sA[cur][1] = *reinterpret_cast<const v4u*>(sa_next + 16);
+            SOLAR_MFMA(s[nxt] = mma32(sA[nxt][1], qB[1], s[nxt]));
+            E(2); sA[cur][2] = *reinterpret_cast<const v4u*>(sa_next + 32);
+            SOLAR_FENCE;
+            E(3); sA[cur][3] = *reinterpret_cast<const v4u*>(sa_next + 48);
+            SOLAR_MFMA(s[nxt] = mma32(sA[nxt][2], qB[2], s[nxt]));
+            E(4); C(0); t0 = lds_read_tr16(za_this);
+            SOLAR_FENCE;
+            E(5); C(1); t1 = lds_read_tr16(za_this + 8 * LDR);
+            SOLAR_MFMA(s[nxt] = mma32(sA[nxt][3], qB[3], s[nxt]));
+            E(6); t2 = lds_read_tr16(za_this + 32);
+            SOLAR_FENCE;
+            E(7); t3 = lds_read_tr16(za_this + 32 + 8 * LDR);
+            SOLAR_MFMA(z[0] = mma32(zA[nxt][0][0], wp[nxt][0], z[0]));
+            zA[cur][0][0] = v4u{t0.x, t0.y, t1.x, t1.y};
+            E(8); C(2);
+            SOLAR_FENCE;
+            E(9); C(3);
+            SOLAR_MFMA(z[1] = mma32(zA[nxt][1][0], wp[nxt][0], z[1]));
+            zA[cur][1][0] = v4u{t2.x, t2.y, t3.x, t3.y};
+            E(10); t0 = lds_read_tr16(za_this + 16 * LDR);
+            SOLAR_FENCE;
+            E(11); t1 = lds_read_tr16(za_this + 24 * LDR);
+            SOLAR_MFMA(z[0] = mma32(zA[nxt][0][1], wp[nxt][1], z[0]));
+            E(12); t2 = lds_read_tr16(za_this + 32 + 16 * LDR);
+            SOLAR_FENCE;
+            E(13); t3 = lds_read_tr16(za_this + 32 + 24 * LDR);
+            SOLAR_MFMA(z[1] = mma32(zA[nxt][1][1], wp[nxt][1], z[1]));
+            SOLAR_MFMA(lacc = mma16(ones, wp[cur][0], lacc));
+            E(14); C(4); X(0);
+            SOLAR_FENCE;
+            E(15); C(5); X(1);
+            SOLAR_FENCE;
+            C(6); C(7);
+            zA[cur][0][1] = v4u{t0.x, t0.y, t1.x, t1.y};
+            zA[cur][1][1] = v4u{t2.x, t2.y, t3.x, t3.y};
+            SOLAR_MFMA(lacc = mma16(ones, wp[cur][1], lacc));
+            X(2); X(3);
+            SOLAR_FENCE;
+#undef SOLAR_MFMA
+        }
     };
 
     // ---- the sequence loop ---------------------------------------------------------------------
@@ -477,12 +551,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     if (nblocks > 0) {
         // S(0) and the reference of the first block; the score operands of block 1
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
+        for (int c = 0; c < NC; ++c) {
             sA[0][c] = *reinterpret_cast<const v4u*>(tiles + sa_off + 16 * c);
             sA[1][c] = *reinterpret_cast<const v4u*>(tiles + 32 * LDR + sa_off + 16 * c);
         }
         s[0] = mma32(sA[0][0], qB[0], cinit);
-        s[0] = mma32(sA[0][1], qB[1], s[0]);
+#pragma unroll
+        for (int c = 1; c < NC; ++c) s[0] = mma32(sA[0][c], qB[c], s[0]);
 #pragma unroll
         for (int t = 0; t < 16; ++t) s[1][t] = 0.f;
         mask_block(0, 0);
@@ -520,11 +595,17 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // Z of the last block trails the loop
     if (nblocks > 0) {
         if ((nblocks - 1) & 1) {
-            z = mma32(zA[1][0], wp[1][0], z);
-            z = mma32(zA[1][1], wp[1][1], z);
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) {
+                z[hh] = mma32(zA[1][hh][0], wp[1][0], z[hh]);
+                z[hh] = mma32(zA[1][hh][1], wp[1][1], z[hh]);
+            }
         } else {
-            z = mma32(zA[0][0], wp[0][0], z);
-            z = mma32(zA[0][1], wp[0][1], z);
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) {
+                z[hh] = mma32(zA[0][hh][0], wp[0][0], z[hh]);
+                z[hh] = mma32(zA[0][hh][1], wp[0][1], z[hh]);
+            }
         }
     }
     };
@@ -548,7 +629,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         const float l = n32 < 16 ? l0 : l1;
         const float inv = l > 0.f ? punscale / l : 0.f;
 #pragma unroll
-        for (int t = 0; t < 16; ++t) z[t] *= inv;
+        for (int t = 0; t < 16; ++t)
+#pragma unroll
+            for (int hh = 0; hh < NH; ++hh) z[hh][t] *= inv;
         const int m = m_wave + n32;
         for (int db = 0; db < D / 32; ++db) {
             v16f o;
@@ -556,8 +639,10 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             for (int t = 0; t < 16; ++t) o[t] = 0.f;
             const float* vrow = Vs + (32 * db + n32) * LDV + 4 * h;
 #pragma unroll
-            for (int t = 0; t < 16; ++t)
-                o = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[8 * (t / 4) + (t % 4)], z[t], o, 0, 0, 0);
+            for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+                for (int t = 0; t < 16; ++t)
+                    o = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32 * hh + 8 * (t / 4) + (t % 4)], z[hh][t], o, 0, 0, 0);
             if (m < M) {
                 float* orow = O + ((size_t)b * M + m) * D + 32 * db + 4 * h;
 #pragma unroll
@@ -568,15 +653,16 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     }
 }
 
-template <int D, bool FUSED>
+template <int D, int RP, bool FUSED>
 hipError_t launch_d(const void* Q, const float* S, const float* V, const void* P, const int32_t* lengths,
                     int B, int N, int r, int M, float scale, float* O, hipStream_t stream) {
     // debugging aid: skip the optimistic pass
     const int guarded_only = std::getenv("SOLAR_X32_GUARDED") != nullptr;
+    constexpr int LDV = RP + 1, kBuf = kNT * (RP + 8);
     const size_t lds = sizeof(float) * (size_t)D * LDV + sizeof(uint16_t) * 3 * (size_t)kBuf + 16 +
                        (FUSED ? sizeof(uint16_t) * 2 * RP * (size_t)(D + 8) : 0);
     dim3 grid(ceil_div(M, kWaves * kQW) * 8 * ceil_div(B, 8)), block(kThreads);
-    auto kern = attention_seq_x32_kernel<D, FUSED>;
+    auto kern = attention_seq_x32_kernel<D, RP, FUSED>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -587,17 +673,27 @@ hipError_t launch_d(const void* Q, const float* S, const float* V, const void* P
 }  // namespace
 
 bool attention_seq_x32_supported(int d, int r) {
-    return (d == 64 || d == 128 || d == 256) && r >= 4 && r <= 32 && (r % 4) == 0;
+    return (d == 64 || d == 128 || d == 256) && r >= 4 && r <= 64 && (r % 4) == 0;
 }
+
+bool attention_seq_x32_from_x_supported(int d, int r) { return attention_seq_x32_supported(d, r) && r <= 32; }
 
 // Q is bf16; S must not be null.
 hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* V, const float* P,
                                     const int32_t* lengths, int B, int N, int d, int r, int M, float scale,
                                     float* O, hipStream_t stream) {
+    if (r <= 32) {
+        switch (d) {
+            case 64: return launch_d<64, 32, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+            case 128: return launch_d<128, 32, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+            case 256: return launch_d<256, 32, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (d) {
-        case 64: return launch_d<64, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
-        case 128: return launch_d<128, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
-        case 256: return launch_d<256, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 64: return launch_d<64, 64, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 128: return launch_d<128, 64, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
+        case 256: return launch_d<256, 64, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -606,10 +702,11 @@ hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* 
 hipError_t launch_attention_seq_x32_from_x(const void* Q, const float* S, const float* V, const void* X,
                                            const int32_t* lengths, int B, int N, int d, int r, int M, float scale,
                                            float* O, hipStream_t stream) {
+    if (r > 32) return hipErrorInvalidValue;
     switch (d) {
-        case 64: return launch_d<64, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
-        case 128: return launch_d<128, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
-        case 256: return launch_d<256, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
+        case 64: return launch_d<64, 32, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
+        case 128: return launch_d<128, 32, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
+        case 256: return launch_d<256, 32, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -63,6 +63,7 @@ hipError_t launch_attention_seq_bf16(const void* Q, const float* S, const float*
 
 // attention_x32.hip
 bool attention_seq_x32_supported(int d, int r);
+bool attention_seq_x32_from_x_supported(int d, int r);
 hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* V, const float* P,
                                     const int32_t* lengths, int B, int N, int d, int r, int M,
                                     float scale, float* O, hipStream_t stream);

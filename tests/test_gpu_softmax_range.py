@@ -46,7 +46,8 @@ def rising_workload(N, d, r, M, seed, ramp_from, factor):
     return w, X
 
 
-@pytest.mark.parametrize("N,d,r,M,ramp_from,factor", [(700, 128, 32, 300, 333, 6.0), (450, 64, 16, 70, 130, 8.0)])
+@pytest.mark.parametrize("N,d,r,M,ramp_from,factor", [(700, 128, 32, 300, 333, 6.0), (450, 64, 16, 70, 130, 8.0),
+                                                           (700, 128, 64, 300, 333, 6.0), (520, 64, 48, 90, 170, 8.0)])
 def test_scores_far_above_the_first_block(lib, oracle, N, d, r, M, ramp_from, factor):
     import torch
     print(f"[case] rising scores N={N} d={d} r={r} M={M}", flush=True)
@@ -71,10 +72,11 @@ def test_scores_far_above_the_first_block(lib, oracle, N, d, r, M, ramp_from, fa
     assert err < 2e-2
 
 
-def test_guarded_pass_alone(lib, oracle):
+@pytest.mark.parametrize("r", [32, 64])
+def test_guarded_pass_alone(lib, oracle, r):
     import torch
-    print("[case] guarded pass alone", flush=True)
-    w = synth.make_workload("t", 3, 1100, 128, 32, 200, synth.BF16, "spectrum", 1.0, 0.01, seed=103)
+    print(f"[case] guarded pass alone r={r}", flush=True)
+    w = synth.make_workload("t", 3, 1100, 128, r, 200, synth.BF16, "spectrum", 1.0, 0.01, seed=103)
     f = oracle.svd_factorize(w.X, w.r, w.lengths)
     db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, True)
     db.factorize()
