@@ -245,7 +245,7 @@ __device__ __forceinline__ void mgs_orthonormalize(float* Zc, float* Qc, float* 
 #pragma unroll
             for (int k = i; k < kPanel; ++k) g[k] = team_sum<TM>(g[k]);
             nrm[i] = g[i];
-            inv[i] = g[i] > dead2 ? 1.f / g[i] : 0.f;
+            inv[i] = g[i] > dead2 ? __builtin_amdgcn_rcpf(g[i]) : 0.f;   // 1 ulp: a projection coefficient
 #pragma unroll
             for (int k = i + 1; k < kPanel; ++k) {
                 const float c = g[k] * inv[i];
@@ -271,12 +271,19 @@ __device__ __forceinline__ void mgs_orthonormalize(float* Zc, float* Qc, float* 
             v4f b[CH];
 #pragma unroll
             for (int k = 0; k < CH; ++k) b[k] = *reinterpret_cast<const v4f*>(zc + 4 * TM * k);
+            // the panel is orthogonal already, so its four projections can all be taken from the
+            // column as it stands (they differ from the one-after-another values by the panel's
+            // loss of orthogonality times rounding): four independent reductions instead of a
+            // chain of four
+            float g[kPanel];
 #pragma unroll
-            for (int i = 0; i < kPanel; ++i) {
-                const float g = team_sum<TM>(dot_ch<CH>(a[i], b)) * inv[i];
+            for (int i = 0; i < kPanel; ++i) g[i] = dot_ch<CH>(a[i], b);
 #pragma unroll
-                for (int k = 0; k < CH; ++k) b[k] -= g * a[i][k];
-            }
+            for (int i = 0; i < kPanel; ++i) g[i] = team_sum<TM>(g[i]) * inv[i];
+#pragma unroll
+            for (int i = 0; i < kPanel; ++i)
+#pragma unroll
+                for (int k = 0; k < CH; ++k) b[k] -= g[i] * a[i][k];
 #pragma unroll
             for (int k = 0; k < CH; ++k) *reinterpret_cast<v4f*>(zc + 4 * TM * k) = b[k];
         }
