@@ -126,8 +126,8 @@ solar_status solar_svd_attention(const void* Q, const float* S, const float* V, 
  * they are used for many.
  *   Q  in [B,M,d] bf16     X  in [B,N,d] bf16     S, V  in  as written by solar_svd_factorize
  *   O  out [B,M,d] float
- * Supported: t = SOLAR_BF16, d in {64, 128, 256}, r <= 32 and a multiple of 4; anything else
- * returns SOLAR_ERR_UNSUPPORTED.  No workspace is used.
+ * Supported: t = SOLAR_BF16, d in {64, 128, 256}, r a multiple of 4, r <= 64 (r <= 32 when d = 256);
+ * anything else returns SOLAR_ERR_UNSUPPORTED.  No workspace is used.
  */
 solar_status solar_svd_attention_from_x(const void* Q, const void* X, const float* S, const float* V,
                                         const int32_t* lengths, int B, int N, int d, int r, int M,

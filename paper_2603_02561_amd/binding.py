@@ -278,7 +278,7 @@ class DeviceBatch:
         return dX
 
     def attention_from_x(self, scale: float, O=None):
-        """Mode 0 with P = X V formed inside the attention kernel (bf16 inputs, r <= 32)."""
+        """Mode 0 with P = X V formed inside the attention kernel (bf16 inputs, r a multiple of 4)."""
         return solar_svd_attention_from_x(self.Q, self.X, self.S, self.V, self.lengths, scale,
                                           self.O if O is None else O)
 

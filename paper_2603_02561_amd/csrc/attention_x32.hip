@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const void* __restrict__ Pin, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
     float scale, int guarded_only, float* __restrict__ O) {
     static_assert(RP == 32 || RP == 64, "one or two 32-rank halves");
-    static_assert(!FUSED || RP == 32, "the fused loader is written for one rank half");
+    static_assert(!FUSED || RP == 32 || D <= 128, "V^T as bf16 head and tail for 64 ranks of d = 256 does not fit LDS");
     constexpr int LDV = RP + 1, LDR = RP + 8, kBuf = kNT * LDR;
     constexpr int NC = RP / 16;   // 16-rank chunks of the score product
     constexpr int NH = RP / 32;   // 32-rank halves of Z
@@ -676,7 +676,9 @@ bool attention_seq_x32_supported(int d, int r) {
     return (d == 64 || d == 128 || d == 256) && r >= 4 && r <= 64 && (r % 4) == 0;
 }
 
-bool attention_seq_x32_from_x_supported(int d, int r) { return attention_seq_x32_supported(d, r) && r <= 32; }
+bool attention_seq_x32_from_x_supported(int d, int r) {
+    return attention_seq_x32_supported(d, r) && (r <= 32 || d <= 128);
+}
 
 // Q is bf16; S must not be null.
 hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* V, const float* P,
@@ -702,7 +704,13 @@ hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* 
 hipError_t launch_attention_seq_x32_from_x(const void* Q, const float* S, const float* V, const void* X,
                                            const int32_t* lengths, int B, int N, int d, int r, int M, float scale,
                                            float* O, hipStream_t stream) {
-    if (r > 32) return hipErrorInvalidValue;
+    if (r > 32) {
+        switch (d) {
+            case 64: return launch_d<64, 64, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
+            case 128: return launch_d<128, 64, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (d) {
         case 64: return launch_d<64, 32, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);
         case 128: return launch_d<128, 32, true>(Q, S, V, X, lengths, B, N, r, M, scale, O, stream);

@@ -32,6 +32,10 @@ CASES = [
     ("d64_r16", synth.make_workload("t", 2, 400, 64, 16, 33, synth.BF16, "gauss_lowrank", seed=106)),
     ("d256_r32", synth.make_workload("t", 2, 700, 256, 32, 100, synth.BF16, "gauss_lowrank", seed=107)),
     ("d128_r4_short", synth.make_workload("t", 2, 37, 128, 4, 5, synth.BF16, "gauss_lowrank", seed=502)),
+    # two rank halves
+    ("d128_r64_varlen", synth.make_workload("t", 3, 900, 128, 64, 130, synth.BF16, "spectrum", 0.5, 0.02,
+                                            var_len=(300, 900), seed=104)),
+    ("d64_r48", synth.make_workload("t", 2, 530, 64, 48, 70, synth.BF16, "gauss_lowrank", seed=505)),
 ]
 
 
@@ -71,15 +75,18 @@ def test_from_x_without_stored_p_and_unsupported(lib, oracle):
     f = oracle.svd_factorize(w.X, w.r, w.lengths)
     want = oracle.svd_attention(w.Q, w.X, f["S"], f["V"], 1.0, 0, w.lengths)
     assert rel_err(db.O.cpu().numpy().astype(np.float64), want) < 2e-2
-    # float inputs and r > 32 are outside this entry point
+    # float inputs, and r > 32 at d = 256 (which the factorization does not take either), are
+    # outside this entry point
     wf = synth.make_workload("t", 1, 100, 64, 8, 9, synth.F32, "gauss_lowrank", seed=503)
     df = lib.DeviceBatch(wf.X, wf.Q, wf.lengths, wf.r, False)
     df.factorize()
     assert lib.solar_svd_attention_from_x(df.Q, df.X, df.S, df.V, df.lengths, 1.0, df.O, raise_on_error=False) == 2
-    w64 = synth.make_workload("t", 1, 200, 128, 64, 9, synth.BF16, "spectrum", 0.5, 0.02, seed=504)
-    d64 = lib.DeviceBatch(w64.X, w64.Q, w64.lengths, 64, True)
+    w64 = synth.make_workload("t", 1, 200, 256, 32, 9, synth.BF16, "spectrum", 0.5, 0.02, seed=504)
+    d64 = lib.DeviceBatch(w64.X, w64.Q, w64.lengths, 32, True)
     d64.factorize()
-    assert lib.solar_svd_attention_from_x(d64.Q, d64.X, d64.S, d64.V, d64.lengths, 1.0, d64.O,
+    V48 = torch.zeros((1, 256, 48), dtype=torch.float32, device="cuda")
+    S48 = torch.ones((1, 48), dtype=torch.float32, device="cuda")
+    assert lib.solar_svd_attention_from_x(d64.Q, d64.X, S48, V48, d64.lengths, 1.0, d64.O,
                                           raise_on_error=False) == 2
     torch.cuda.synchronize()
 
