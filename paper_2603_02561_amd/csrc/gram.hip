@@ -170,31 +170,23 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
             }
         }
     } else {
-        const float* X = reinterpret_cast<const float*>(Xv) + (size_t)b * N * D;
-        float cur[4][CPL], nxt[4][CPL];
-        auto load = [&](float (&dst)[4][CPL], int base) {
+        // float inputs: the same ring of row blocks (16 rows per block: lane (j, h) holds rows
+        // 4t + h, t = 0..3, and the loaded values are the MFMA operands as they stand)
+        const float* X = reinterpret_cast<const float*>(Xv) + (size_t)b * N * D + CPL * j;
+        const int row_max = max(r1 - 1, 0);
+        auto load = [&](float (&dst)[4][CPL], int base) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const int row = base + 4 * t + h;
-                if (row < r1) {
-                    const float* p = X + (size_t)row * D + CPL * j;
+                const float* p = X + (size_t)min(base + 4 * t + h, row_max) * D;
 #pragma unroll
-                    for (int q = 0; q < CPL / 4; ++q) {
-                        v4f v = *reinterpret_cast<const v4f*>(p + 4 * q);
-                        dst[t][4 * q + 0] = v.x; dst[t][4 * q + 1] = v.y;
-                        dst[t][4 * q + 2] = v.z; dst[t][4 * q + 3] = v.w;
-                    }
-                } else {
-#pragma unroll
-                    for (int s = 0; s < CPL; ++s) dst[t][s] = 0.f;
+                for (int q = 0; q < CPL / 4; ++q) {
+                    const v4f v = *reinterpret_cast<const v4f*>(p + 4 * q);
+                    dst[t][4 * q + 0] = v.x; dst[t][4 * q + 1] = v.y;
+                    dst[t][4 * q + 2] = v.z; dst[t][4 * q + 3] = v.w;
                 }
             }
         };
-        int base = r0 + wave * STEP;
-        if (base < r1) load(cur, base);
-        while (base < r1) {
-            const int nbase = base + kGramWaves * STEP;
-            if (nbase < r1) load(nxt, nbase);
+        auto compute = [&](const float (&src)[4][CPL]) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 int p = 0;
@@ -202,17 +194,44 @@ __global__ __launch_bounds__(kGramWaves * 64) void gram_partial_kernel(
                 for (int s1 = 0; s1 < CPL; ++s1)
 #pragma unroll
                     for (int s2 = s1; s2 < CPL; ++s2) {
-                        acc[p] = mfma16x16x4(cur[t][s1], cur[t][s2], acc[p]);
+                        acc[p] = mfma16x16x4(src[t][s1], src[t][s2], acc[p]);
                         ++p;
                     }
             }
-            if (nbase < r1) {
+        };
+        auto compute_tail = [&](float (&src)[4][CPL], int base) __attribute__((always_inline)) {
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < 4; ++t)
+                if (base + 4 * t + h >= r1) {
 #pragma unroll
-                    for (int s = 0; s < CPL; ++s) cur[t][s] = nxt[t][s];
+                    for (int s = 0; s < CPL; ++s) src[t][s] = 0.f;
+                }
+            compute(src);
+        };
+        constexpr int kRing = SOLAR_GRAM_RING;
+        float ring[kRing][4][CPL];
+        constexpr int stride = kGramWaves * STEP;
+        const int base0 = r0 + wave * STEP;
+        const int nblk = base0 < r1 ? ceil_div(r1 - base0, stride) : 0;
+        const int nwhole = r1 - base0 >= STEP ? (r1 - base0 - STEP) / stride + 1 : 0;
+#pragma unroll
+        for (int k = 0; k < kRing - 1; ++k) load(ring[k], base0 + k * stride);
+        int i = 0;
+        for (; i + kRing <= nwhole; i += kRing) {
+#pragma unroll
+            for (int k = 0; k < kRing; ++k) {
+                load(ring[(k + kRing - 1) % kRing], base0 + (i + k + kRing - 1) * stride);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(ring[k]);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            base = nbase;
+        }
+#pragma unroll
+        for (int k = 0; k < kRing; ++k) {
+            if (i + k < nblk) {
+                if (i + k + kRing - 1 < nblk) load(ring[(k + kRing - 1) % kRing], base0 + (i + k + kRing - 1) * stride);
+                compute_tail(ring[k], base0 + (i + k) * stride);
+            }
         }
     }
 
