@@ -16,6 +16,8 @@
 //
 // attention_tokens_kernel -- the literal r-token form, with or without softmax:
 //   O = softmax_k(scale * Q T^T) T   or   O = scale * (Q T^T) T,   T = diag(S) V^T.
+#include <cstdlib>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -33,8 +35,12 @@ constexpr float kLog2e = 1.4426950408889634f;
 // is reused as a B operand, which keeps those reads free of bank conflicts.
 __device__ __forceinline__ int rank_perm(int i) { return (i >> 2) + 4 * (i & 3); }
 
-template <int D, int RB, bool BF16, int QB>
-__global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
+// NS > 1: the workgroup has NS groups of four waves; group sp takes every NS-th tile of the
+// sequence for the same queries and the groups' partial results (reference, row sum, Z) are
+// merged in a fixed order at the end.  It gives a small batch, whose workgroups do not fill the
+// GPU's wave slots, NS independent chains of products and exponentials per SIMD.
+template <int D, int RB, bool BF16, int QB, int NS>
+__global__ __launch_bounds__(kAttnThreads * NS) void attention_seq_kernel(
     const void* __restrict__ Qv, const float* __restrict__ V, const float* __restrict__ P,
     const int32_t* __restrict__ lengths, int B, int N, int r, int M, float scale, float* __restrict__ O) {
     constexpr int RP = 16 * RB;
@@ -42,25 +48,28 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
     constexpr int LDP = RP + 4;
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* Vs = smem;                       // [D][LDV]
-    float* Ps = Vs + D * LDV;               // [2][kNT][LDP]
+    float* Ps = Vs + D * LDV;               // [2][NS][kNT][LDP]
+    constexpr int NTHR = kAttnThreads * NS;
     // Workgroups are dealt to the 8 XCDs round-robin by linear id.  All M-tiles of a user
     // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
     const int mtiles = ceil_div(M, 4 * QB * 16);
     const int slot = blockIdx.x >> 3;
     const int b = (slot / mtiles) * 8 + (blockIdx.x & 7);
     if (b >= B) return;   // uniform over the workgroup
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = (tid >> 6) & 3;        // query group of the wave
+    const int sp = tid >> 8;                // its share of the sequence (0 when NS == 1)
     const int i16 = lane & 15, g = lane >> 4;
     const int len = user_len(lengths, b, N);
     const int m_wave = (slot % mtiles) * (4 * QB * 16) + wave * (QB * 16);
     const float* Pb = P + (size_t)b * N * r;
 
-    for (int e = tid; e < D * RP; e += kAttnThreads) {
+    for (int e = tid; e < D * RP; e += NTHR) {
         const int k = e / RP, c = e % RP;
         Vs[k * LDV + c] = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
     }
     // zero both P tiles once so that the padded rank columns stay zero
-    for (int e = tid; e < 2 * kNT * LDP; e += kAttnThreads) Ps[e] = 0.f;
+    for (int e = tid; e < 2 * NS * kNT * LDP; e += NTHR) Ps[e] = 0.f;
     __syncthreads();
 
     // ---- prologue: Qt^T = V^T Q^T, scaled by scale*log2(e) -------------------------
@@ -104,21 +113,22 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
         for (int ib = 0; ib < RB; ++ib) z[qb][ib] = v4f{0.f, 0.f, 0.f, 0.f};
     }
 
-    const int ntiles = ceil_div(len, kNT);
-    // A tile is kNT*r consecutive floats of P; each thread moves `kLoads` float4 (r % 4 == 0)
-    // or falls back to scalars.
+    const int ntiles = ceil_div(ceil_div(len, kNT), NS);   // steps of NS tiles
+    constexpr int kRows = NS * kNT;                        // rows loaded per step
+    // A step is kRows*r consecutive floats of P; a thread moves float4 (r % 4 == 0) or falls
+    // back to scalars.
     auto load_tile = [&](int tile, float* dst) {
-        const int n0 = tile * kNT;
+        const int n0 = tile * kRows;
         if ((r & 3) == 0) {
             const int quads_per_row = r >> 2;
-            for (int e = tid; e < kNT * quads_per_row; e += kAttnThreads) {
+            for (int e = tid; e < kRows * quads_per_row; e += NTHR) {
                 const int nn = e / quads_per_row, c4 = e % quads_per_row;
                 v4f v = v4f{0.f, 0.f, 0.f, 0.f};
                 if (n0 + nn < len) v = *reinterpret_cast<const v4f*>(Pb + (size_t)(n0 + nn) * r + 4 * c4);
                 *reinterpret_cast<v4f*>(dst + nn * LDP + 4 * c4) = v;
             }
         } else {
-            for (int e = tid; e < kNT * r; e += kAttnThreads) {
+            for (int e = tid; e < kRows * r; e += NTHR) {
                 const int nn = e / r, c = e % r;
                 dst[nn * LDP + c] = (n0 + nn < len) ? Pb[(size_t)(n0 + nn) * r + c] : 0.f;
             }
@@ -128,9 +138,10 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
     __syncthreads();
 
     for (int tile = 0; tile < ntiles; ++tile) {
-        const float* pt = Ps + (tile & 1) * (kNT * LDP);
-        if (tile + 1 < ntiles) load_tile(tile + 1, Ps + ((tile + 1) & 1) * (kNT * LDP));
-        const int n0 = tile * kNT;
+        const float* pt = Ps + ((tile & 1) * NS + sp) * (kNT * LDP);
+        if (tile + 1 < ntiles) load_tile(tile + 1, Ps + ((tile + 1) & 1) * (kRows * LDP));
+        const int n0 = (tile * NS + sp) * kNT;
+        if (n0 < len) {   // uniform over the wave: only the last step can leave a group without rows
 
         // scores S^T[n][m] for the 4 blocks of 16 rows
         v4f s[QB][kNT / 16];
@@ -200,7 +211,47 @@ __global__ __launch_bounds__(kAttnThreads) void attention_seq_kernel(
                         z[qb][ib] = mfma16x16x4(a, s[qb][nb][t], z[qb][ib]);
                 }
             }
+        }
         __syncthreads();
+    }
+
+    // ---- merge of the sequence shares (group 0 takes the others in order) -----------------
+    if constexpr (NS > 1) {
+        constexpr int kState = QB * (4 * RB + 2);   // floats per lane
+        float* st = Ps;                              // [NS-1][4 waves][kState][64 lanes]
+        if (sp > 0) {
+            float* mine = st + ((sp - 1) * 4 + wave) * (kState * 64) + lane;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                mine[(qb * (4 * RB + 2) + 0) * 64] = mrun[qb];
+                mine[(qb * (4 * RB + 2) + 1) * 64] = lrun[qb];
+#pragma unroll
+                for (int ib = 0; ib < RB; ++ib)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) mine[(qb * (4 * RB + 2) + 2 + 4 * ib + t) * 64] = z[qb][ib][t];
+            }
+        }
+        __syncthreads();
+        if (sp > 0) return;
+        for (int o = 0; o < NS - 1; ++o) {
+            const float* other = st + (o * 4 + wave) * (kState * 64) + lane;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const float mo = other[(qb * (4 * RB + 2) + 0) * 64];
+                const float lo = other[(qb * (4 * RB + 2) + 1) * 64];
+                const float mnew = fmaxf(mrun[qb], mo);
+                // a share without rows has reference -inf and contributes nothing
+                const float a0 = mrun[qb] > -INFINITY ? __builtin_amdgcn_exp2f(mrun[qb] - mnew) : 0.f;
+                const float a1 = mo > -INFINITY ? __builtin_amdgcn_exp2f(mo - mnew) : 0.f;
+                mrun[qb] = mnew;
+                lrun[qb] = lrun[qb] * a0 + lo * a1;
+#pragma unroll
+                for (int ib = 0; ib < RB; ++ib)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        z[qb][ib][t] = z[qb][ib][t] * a0 + other[(qb * (4 * RB + 2) + 2 + 4 * ib + t) * 64] * a1;
+            }
+        }
     }
 
     // ---- epilogue: O^T = V (Z / l)^T ------------------------------------------------
@@ -285,21 +336,21 @@ __global__ __launch_bounds__(256) void attention_tokens_kernel(
 
 }  // namespace
 
-template <int D, int RB, int QB>
+template <int D, int RB, int QB, int NS>
 static hipError_t launch_seq_q(const void* Q, const float* V, const float* P,
                                const int32_t* lengths, int B, int N, int r, int M, float scale,
                                bool bf16, float* O, hipStream_t stream) {
     constexpr int RP = 16 * RB;
-    const size_t lds = sizeof(float) * ((size_t)D * (RP + 4) + 2 * kNT * (RP + 4));
-    dim3 grid(ceil_div(M, 4 * QB * 16) * 8 * ceil_div(B, 8)), block(kAttnThreads);
+    const size_t lds = sizeof(float) * ((size_t)D * (RP + 4) + 2 * NS * kNT * (RP + 4));
+    dim3 grid(ceil_div(M, 4 * QB * 16) * 8 * ceil_div(B, 8)), block(kAttnThreads * NS);
     if (bf16) {
-        auto kern = attention_seq_kernel<D, RB, true, QB>;
+        auto kern = attention_seq_kernel<D, RB, true, QB, NS>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
     } else {
-        auto kern = attention_seq_kernel<D, RB, false, QB>;
+        auto kern = attention_seq_kernel<D, RB, false, QB, NS>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -309,14 +360,43 @@ static hipError_t launch_seq_q(const void* Q, const float* V, const float* P,
 }
 
 // A wave takes two 16-query blocks (each row of P read from LDS serves both) unless that leaves
-// fewer workgroups than compute units; then one block per wave fills the GPU.
+// fewer workgroups than compute units; then one block per wave fills the GPU.  If the workgroups
+// of four waves still leave the SIMDs with fewer than four waves each, the sequence is shared
+// out among two or four groups of waves per workgroup (as far as the tile buffers fit LDS).
+template <int D, int RB, int QB>
+static hipError_t launch_seq_n(const void* Q, const float* V, const float* P,
+                               const int32_t* lengths, int B, int N, int r, int M, float scale,
+                               bool bf16, float* O, hipStream_t stream) {
+    const long long wgs = (long long)B * ceil_div(M, 64 * QB);
+    int ns = wgs >= 1024 ? 1 : (wgs >= 512 ? 2 : 4);
+    static const int forced = [] {
+        const char* e = std::getenv("SOLAR_ATTN_NS");   // tuning aid
+        return e ? std::atoi(e) : 0;
+    }();
+    if (forced == 1 || forced == 2 || forced == 4) ns = forced;
+    // two query blocks per wave leave room for two groups only (four would hold 16 waves to 128
+    // registers each, which that variant does not fit; nor does it fit 256 at d = 256, r > 48)
+    constexpr int kMaxNs = QB == 1 ? 4 : ((D == 256 && RB == 4) ? 1 : 2);
+    if (ns > kMaxNs) ns = kMaxNs;
+    constexpr size_t row = sizeof(float) * (16 * RB + 4);
+    while (ns > 1 && D * row + 2 * ns * kNT * row > 150 * 1024) ns /= 2;
+    while (ns > 1 && N <= (ns / 2) * kNT) ns /= 2;   // no more groups than tiles
+    if constexpr (kMaxNs >= 4) {
+        if (ns == 4) return launch_seq_q<D, RB, QB, 4>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+    }
+    if constexpr (kMaxNs >= 2) {
+        if (ns == 2) return launch_seq_q<D, RB, QB, 2>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+    }
+    return launch_seq_q<D, RB, QB, 1>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+}
+
 template <int D, int RB>
 static hipError_t launch_seq_t(const void* Q, const float* V, const float* P,
                                const int32_t* lengths, int B, int N, int r, int M, float scale,
                                bool bf16, float* O, hipStream_t stream) {
     if ((long long)B * ceil_div(M, 128) < 256)
-        return launch_seq_q<D, RB, 1>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
-    return launch_seq_q<D, RB, 2>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+        return launch_seq_n<D, RB, 1>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
+    return launch_seq_n<D, RB, 2>(Q, V, P, lengths, B, N, r, M, scale, bf16, O, stream);
 }
 
 template <int D>

@@ -246,6 +246,7 @@ EDGE = [
     ("nine_users_bf16", 9, 130, 128, 16, 17, synth.BF16, None),
     ("one_row_tail_tile", 2, 129, 128, 32, 257, synth.BF16, [129, 65]),
     ("r_is_d", 1, 200, 64, 64, 20, synth.F32, None),
+    ("many_users_two_query_blocks", 64, 200, 64, 8, 520, synth.F32, [8 + (37 * i) % 193 for i in range(64)]),
 ]
 
 
@@ -253,7 +254,9 @@ EDGE = [
 def test_edge_shapes(lib, oracle, name, B, N, d, r, M, dtype, lengths):
     """Degenerate and ragged shapes: fewer rows than a tile, a single candidate, a valid length
     equal to the rank, a batch that does not fill the 8-way workgroup ordering, a one-row last
-    tile, and r = d (no truncation: SVD-Attention is dense attention for any X)."""
+    tile, r = d (no truncation: SVD-Attention is dense attention for any X), and a float batch
+    with enough users for two query blocks per wave yet few enough workgroups for the sequence
+    to be shared out inside them (lengths from 8 rows to two and more tiles)."""
     import torch
     print(f"[case] edge {name}", flush=True)
     kind = "gauss_lowrank" if name != "r_is_d" else "spectrum"
