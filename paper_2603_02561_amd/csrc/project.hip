@@ -7,6 +7,8 @@
 // four values are the B operand of four successive MFMAs; the matching rows of V
 // come from LDS.  The result tile leaves the matrix unit with four consecutive
 // rank indices per lane, i.e. as one 16-byte store into the row-major P.
+#include <cstdlib>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -15,12 +17,12 @@ namespace solar {
 namespace {
 
 constexpr int kProjThreads = 256;
-constexpr int kProjTilesPerWave = 8;  // 16-row tiles handled by one wave
+constexpr int kProjTilesPerWave = 8;  // 16-row tiles handled by one wave (fewer in small launches)
 
 template <int D, bool BF16>
 __global__ __launch_bounds__(kProjThreads) void project_kernel(
     const void* __restrict__ Xv, const int32_t* __restrict__ lengths, const float* __restrict__ V,
-    int N, int r, int RP, float* __restrict__ P) {
+    int N, int r, int RP, int tiles_per_wave, float* __restrict__ P) {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const int LDV = RP + 4;
     float* Vs = smem;  // [D][LDV], columns >= r are zero
@@ -36,10 +38,10 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(
     }
     __syncthreads();
 
-    const int rows_per_block = 16 * 4 * kProjTilesPerWave;
+    const int rows_per_block = 16 * 4 * tiles_per_wave;
     const int block_row0 = blockIdx.x * rows_per_block;
     float* Pb = P + (size_t)b * N * r;
-    for (int tile = 0; tile < kProjTilesPerWave; ++tile) {
+    for (int tile = 0; tile < tiles_per_wave; ++tile) {
         const int n0 = block_row0 + (tile * 4 + wave) * 16;
         if (n0 >= N) break;
         const int n = n0 + i16;
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(
 template <int D, int RB>
 __global__ __launch_bounds__(kProjThreads) void project_bf16_kernel(
     const uint16_t* __restrict__ X, const int32_t* __restrict__ lengths, const float* __restrict__ V,
-    int N, int r, float* __restrict__ P) {
+    int N, int r, int tiles_per_wave, float* __restrict__ P) {
     constexpr int KK = D / 32;
     const int b = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(kProjThreads) void project_bf16_kernel(
             alo[kk][rb] = v4u{lw[0], lw[1], lw[2], lw[3]};
         }
 
-    const int rows_per_block = 16 * 4 * kProjTilesPerWave;
+    const int rows_per_block = 16 * 4 * tiles_per_wave;
     const int block_row0 = blockIdx.x * rows_per_block;
     const uint16_t* Xb = X + (size_t)b * N * D;
     float* Pb = P + (size_t)b * N * r;
@@ -156,10 +158,10 @@ __global__ __launch_bounds__(kProjThreads) void project_bf16_kernel(
     v4u cur[KK], nxt[KK];
     int n0 = block_row0 + wave * 16;
     if (n0 < len) fetch(cur, n0);
-    for (int tile = 0; tile < kProjTilesPerWave; ++tile) {
+    for (int tile = 0; tile < tiles_per_wave; ++tile) {
         if (n0 >= N) break;
         const int n_next = n0 + 64;
-        const bool have_next = tile + 1 < kProjTilesPerWave && n_next < len;
+        const bool have_next = tile + 1 < tiles_per_wave && n_next < len;
         if (have_next) fetch(nxt, n_next);
         const int n = n0 + i16;
         if (n0 >= len) {
@@ -205,16 +207,28 @@ static hipError_t launch_project_d(const void* X, const int32_t* lengths, const 
                                    int N, int r, bool bf16, float* P, hipStream_t stream) {
     const int RP = 16 * ((r + 15) / 16);
     const size_t lds = sizeof(float) * (size_t)D * (RP + 4);
-    dim3 grid(ceil_div(N, 16 * 4 * kProjTilesPerWave), B), block(kProjThreads);
+    // A wave takes eight 16-row tiles when that still gives every SIMD four waves (float
+    // kernel, which has no prefetch and hides its loads behind other waves) or every compute
+    // unit a workgroup (bf16 kernel, where a wave first builds its operands of V and wants
+    // many tiles to spread that over); smaller launches take fewer tiles per wave.
+    const long long want = bf16 ? 256 : 1024;
+    int tiles = kProjTilesPerWave;
+    while (tiles > 1 && (long long)B * ceil_div(N, 64 * tiles) < want) tiles /= 2;
+    static const int forced = [] {
+        const char* e = std::getenv("SOLAR_PROJECT_TILES");   // tuning aid
+        return e ? std::atoi(e) : 0;
+    }();
+    if (forced >= 1 && forced <= 8) tiles = forced;
+    dim3 grid(ceil_div(N, 16 * 4 * tiles), B), block(kProjThreads);
     if (bf16) {
         const uint16_t* Xh = reinterpret_cast<const uint16_t*>(X);
         switch (RP / 16) {
-            case 1: hipLaunchKernelGGL((project_bf16_kernel<D, 1>), grid, block, 0, stream, Xh, lengths, V, N, r, P); break;
-            case 2: hipLaunchKernelGGL((project_bf16_kernel<D, 2>), grid, block, 0, stream, Xh, lengths, V, N, r, P); break;
-            case 3: hipLaunchKernelGGL((project_bf16_kernel<D, 3>), grid, block, 0, stream, Xh, lengths, V, N, r, P); break;
+            case 1: hipLaunchKernelGGL((project_bf16_kernel<D, 1>), grid, block, 0, stream, Xh, lengths, V, N, r, tiles, P); break;
+            case 2: hipLaunchKernelGGL((project_bf16_kernel<D, 2>), grid, block, 0, stream, Xh, lengths, V, N, r, tiles, P); break;
+            case 3: hipLaunchKernelGGL((project_bf16_kernel<D, 3>), grid, block, 0, stream, Xh, lengths, V, N, r, tiles, P); break;
             case 4:
                 if constexpr (D <= 128) {
-                    hipLaunchKernelGGL((project_bf16_kernel<D, 4>), grid, block, 0, stream, Xh, lengths, V, N, r, P);
+                    hipLaunchKernelGGL((project_bf16_kernel<D, 4>), grid, block, 0, stream, Xh, lengths, V, N, r, tiles, P);
                     break;
                 }
                 [[fallthrough]];
@@ -223,7 +237,7 @@ static hipError_t launch_project_d(const void* X, const int32_t* lengths, const 
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
                 if (e != hipSuccess) return e;
-                hipLaunchKernelGGL(kern, grid, block, lds, stream, X, lengths, V, N, r, RP, P);
+                hipLaunchKernelGGL(kern, grid, block, lds, stream, X, lengths, V, N, r, RP, tiles, P);
             }
         }
     } else {
@@ -231,7 +245,7 @@ static hipError_t launch_project_d(const void* X, const int32_t* lengths, const 
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, block, lds, stream, X, lengths, V, N, r, RP, P);
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, X, lengths, V, N, r, RP, tiles, P);
     }
     return hipGetLastError();
 }
