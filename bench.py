@@ -123,8 +123,8 @@ def latency_sweep(w, steps: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default=WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-users", type=int, default=8)
@@ -373,7 +373,7 @@ def main() -> int:
                                nbytes / (ms * 1e-3) / 1e9 / PEAKS["hbm_GBps"]}
         del dX
     if args.sweep:
-        out["sweep"] = latency_sweep(w, args.steps)
+        out["sweep"] = latency_sweep(w, min(args.steps, 20))   # its dense reference kernel takes 50 ms at N = 20000
     if not args.no_cpu_baseline:
         n_cpu = min(args.cpu_users, w.B)
         base, o_cpu = cpu_baseline(w, n_cpu)
