@@ -78,6 +78,10 @@ __device__ __forceinline__ v16f mma32(v4u a, v4u b, v16f c) {
                                                   0, 0, 0);
 }
 
+__device__ __forceinline__ v16f mma32bf(v4u a, v4u b, v16f c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+}
+
 __device__ __forceinline__ v4f mma16(v4u a, v4u b, v4f c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c,
                                                   0, 0, 0);
@@ -118,16 +122,19 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const void* __restrict__ Pin, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
     float scale, int guarded_only, float* __restrict__ O) {
     static_assert(RP == 32 || RP == 64, "one or two 32-rank halves");
-    static_assert(!FUSED || RP == 32 || D <= 128, "V^T as bf16 head and tail for 64 ranks of d = 256 does not fit LDS");
-    constexpr int LDV = RP + 1, LDR = RP + 8, kBuf = kNT * LDR;
+    static_assert(RP == 32 || D <= 128, "the bf16 images of V for 64 ranks of d = 256 do not fit LDS");
+    constexpr int LDR = RP + 8, kBuf = kNT * LDR;
     constexpr int NC = RP / 16;   // 16-rank chunks of the score product
     constexpr int NH = RP / 32;   // 32-rank halves of Z
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    float* Vs = smem;                                              // [D][LDV]
-    uint16_t* tiles = reinterpret_cast<uint16_t*>(Vs + D * LDV);   // [3][kBuf]
+    // V as bf16 head (truncated, so the remainder is exact) and tail, in the two orders the
+    // matrix unit wants it: transposed for Qt^T = V^T Q^T (and the fused projection), and row
+    // by row with the rank quads in the order of the tile images for O^T = V Z^T
+    constexpr int LDVT = D + 8, LDI = RP + 8;                      // bf16 elements
+    uint16_t* tiles = reinterpret_cast<uint16_t*>(smem);           // [3][kBuf]
     int* redo = reinterpret_cast<int*>(tiles + 3 * kBuf);          // set when a wave's optimistic pass overflowed
-    constexpr int LDVT = D + 8;                                    // bf16 elements
-    uint16_t* vt = reinterpret_cast<uint16_t*>(redo + 4);          // FUSED: [2][RP][LDVT], V^T as bf16 head and tail
+    uint16_t* vt = reinterpret_cast<uint16_t*>(redo + 4);          // [2][RP][LDVT]
+    uint16_t* vimg = vt + 2 * RP * LDVT;                           // [2][D][LDI]
     // Workgroups are dealt to the 8 XCDs round-robin by linear id.  All M-tiles of a user
     // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
     const int mtiles = ceil_div(M, kWaves * kQW);
@@ -148,29 +155,26 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         if (rescale) { pscale = 1.f / s0; punscale = s0; }
     }
 
-    for (int e = tid; e < D * RP; e += kThreads) {
-        const int k = e / RP, c = e % RP;
-        Vs[k * LDV + c] = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
-    }
     // zero the tile buffers once: padded rank columns stay zero for ever
     for (int e = tid; e < 3 * kBuf / 2; e += kThreads) reinterpret_cast<uint32_t*>(tiles)[e] = 0u;
     if (tid == 0) *redo = 0;
-    if constexpr (FUSED) {
-        // V^T split into a bf16 head (truncated, so the remainder is exact) and a bf16 tail
-        for (int e = tid; e < RP * D; e += kThreads) {
-            const int c = e / D, k = e % D;
-            const float v = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
-            const uint32_t hi = __float_as_uint(v) & 0xffff0000u;
-            const float rem = v - __uint_as_float(hi);
-            const uint32_t lo = (__float_as_uint(rem) + 0x7fffu + ((__float_as_uint(rem) >> 16) & 1u)) >> 16;
-            vt[c * LDVT + k] = (uint16_t)(hi >> 16);
-            vt[(RP + c) * LDVT + k] = (uint16_t)lo;
-        }
+    for (int e = tid; e < D * RP; e += kThreads) {
+        const int k = e / RP, c = e % RP;   // consecutive threads read consecutive ranks of a row of V
+        const float v = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
+        const uint32_t hi = __float_as_uint(v) & 0xffff0000u;
+        const float rem = v - __uint_as_float(hi);
+        const uint32_t lo = (__float_as_uint(rem) + 0x7fffu + ((__float_as_uint(rem) >> 16) & 1u)) >> 16;
+        vt[c * LDVT + k] = (uint16_t)(hi >> 16);
+        vt[(RP + c) * LDVT + k] = (uint16_t)lo;
+        const int pos = 4 * quad_pos(c >> 2) + (c & 3);
+        vimg[k * LDI + pos] = (uint16_t)(hi >> 16);
+        vimg[(D + k) * LDI + pos] = (uint16_t)lo;
     }
     __syncthreads();
 
-    // ---- prologue: Qt^T = V^T Q^T in float (32x32x2 MFMA; the contraction slot of lane half
-    // h in step s is coordinate (D/2)*h + s), scaled by scale*log2(e), rounded to fp16 -------
+    // ---- prologue: Qt^T = V^T Q^T on the 32x32x16 bf16 MFMA (head and tail of V against the
+    // bf16 queries as they are: both contraction operands are 16-byte reads), scaled by
+    // scale*log2(e), rounded to fp16 ----------------------------------------------------------
     v4u qB[NC];
     {
         v16f qt[NH];
@@ -180,21 +184,16 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             for (int t = 0; t < 16; ++t) qt[hh][t] = 0.f;
         const int m = m_wave + n32;
         const bool valid = m < M;
-        const uint16_t* qrow = reinterpret_cast<const uint16_t*>(Qv) + ((size_t)b * M + (valid ? m : 0)) * D +
-                               (D / 2) * h;
-        const float* vcol = Vs + (D / 2) * h * LDV + n32;
-        for (int cc = 0; cc < D / 16; ++cc) {
-            v4u w = *reinterpret_cast<const v4u*>(qrow + 8 * cc);
+        const uint16_t* qrow = reinterpret_cast<const uint16_t*>(Qv) + ((size_t)b * M + (valid ? m : 0)) * D + 8 * h;
+        const uint16_t* va = vt + n32 * LDVT + 8 * h;
+#pragma unroll 4
+        for (int kk = 0; kk < D / 16; ++kk) {
+            v4u w = *reinterpret_cast<const v4u*>(qrow + 16 * kk);
             if (!valid) w = v4u{0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-#pragma unroll
-                for (int hh = 0; hh < NH; ++hh) {
-                    qt[hh] = __builtin_amdgcn_mfma_f32_32x32x2f32(vcol[(8 * cc + 2 * e) * LDV + 32 * hh], bf16_lo(w[e]),
-                                                                  qt[hh], 0, 0, 0);
-                    qt[hh] = __builtin_amdgcn_mfma_f32_32x32x2f32(vcol[(8 * cc + 2 * e + 1) * LDV + 32 * hh],
-                                                                  bf16_hi(w[e]), qt[hh], 0, 0, 0);
-                }
+            for (int hh = 0; hh < NH; ++hh) {
+                qt[hh] = mma32bf(*reinterpret_cast<const v4u*>(va + (32 * hh) * LDVT + 16 * kk), w, qt[hh]);
+                qt[hh] = mma32bf(*reinterpret_cast<const v4u*>(va + (RP + 32 * hh) * LDVT + 16 * kk), w, qt[hh]);
             }
         }
         // B operand of the score product, chunk c: slot u of lane half h is register 8*(c%2) + u of
@@ -622,27 +621,46 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     }
 #undef SOLAR_FENCE
 
-    // ---- epilogue in float: O^T = V (Z / l)^T with the 32x32x2 MFMA: step t contracts the
-    // ranks of register t (one per lane half) -----------------------------------------------------
+    // ---- epilogue: O^T = V (Z / l)^T on the bf16 MFMA with head and tail of both operands
+    // (the tail-tail term, 2^-16 of the result, is dropped); chunk c of the contraction takes the
+    // ranks of registers 8*(c%2) .. +7 of rank half c/2, which the V image lists in the same order
     {
-        const float l0 = __shfl(lacc[0], n32 & 15), l1 = __shfl(lacc[1], n32 & 15);
-        const float l = n32 < 16 ? l0 : l1;
+        float l;
+        {
+            const float l0 = __shfl(lacc[0], n32 & 15), l1 = __shfl(lacc[1], n32 & 15);
+            l = n32 < 16 ? l0 : l1;
+        }
         const float inv = l > 0.f ? punscale / l : 0.f;
+        v4u zh[NC], zl[NC];
 #pragma unroll
-        for (int t = 0; t < 16; ++t)
+        for (int c = 0; c < NC; ++c) {
+            uint32_t hw[4], lw[4];
 #pragma unroll
-            for (int hh = 0; hh < NH; ++hh) z[hh][t] *= inv;
+            for (int u2 = 0; u2 < 4; ++u2) {
+                const float a0 = z[c / 2][8 * (c % 2) + 2 * u2] * inv, a1 = z[c / 2][8 * (c % 2) + 2 * u2 + 1] * inv;
+                const uint32_t h0 = __float_as_uint(a0) & 0xffff0000u, h1 = __float_as_uint(a1) & 0xffff0000u;
+                hw[u2] = (h0 >> 16) | h1;
+                typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+                const v2bf t = {(__bf16)(a0 - __uint_as_float(h0)), (__bf16)(a1 - __uint_as_float(h1))};
+                lw[u2] = __builtin_bit_cast(uint32_t, t);
+            }
+            zh[c] = v4u{hw[0], hw[1], hw[2], hw[3]};
+            zl[c] = v4u{lw[0], lw[1], lw[2], lw[3]};
+        }
         const int m = m_wave + n32;
         for (int db = 0; db < D / 32; ++db) {
             v16f o;
 #pragma unroll
             for (int t = 0; t < 16; ++t) o[t] = 0.f;
-            const float* vrow = Vs + (32 * db + n32) * LDV + 4 * h;
+            const uint16_t* vh = vimg + (32 * db + n32) * LDI + 8 * h;
 #pragma unroll
-            for (int hh = 0; hh < NH; ++hh)
-#pragma unroll
-                for (int t = 0; t < 16; ++t)
-                    o = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32 * hh + 8 * (t / 4) + (t % 4)], z[hh][t], o, 0, 0, 0);
+            for (int c = 0; c < NC; ++c) {
+                const v4u ah = *reinterpret_cast<const v4u*>(vh + 16 * c);
+                const v4u al = *reinterpret_cast<const v4u*>(vh + D * LDI + 16 * c);
+                o = mma32bf(ah, zh[c], o);
+                o = mma32bf(ah, zl[c], o);
+                o = mma32bf(al, zh[c], o);
+            }
             if (m < M) {
                 float* orow = O + ((size_t)b * M + m) * D + 32 * db + 4 * h;
 #pragma unroll
@@ -658,9 +676,8 @@ hipError_t launch_d(const void* Q, const float* S, const float* V, const void* P
                     int B, int N, int r, int M, float scale, float* O, hipStream_t stream) {
     // debugging aid: skip the optimistic pass
     const int guarded_only = std::getenv("SOLAR_X32_GUARDED") != nullptr;
-    constexpr int LDV = RP + 1, kBuf = kNT * (RP + 8);
-    const size_t lds = sizeof(float) * (size_t)D * LDV + sizeof(uint16_t) * 3 * (size_t)kBuf + 16 +
-                       (FUSED ? sizeof(uint16_t) * 2 * RP * (size_t)(D + 8) : 0);
+    constexpr int kBuf = kNT * (RP + 8);
+    const size_t lds = sizeof(uint16_t) * (3 * (size_t)kBuf + 2 * RP * (size_t)(D + 8) + 2 * D * (size_t)(RP + 8)) + 16;
     dim3 grid(ceil_div(M, kWaves * kQW) * 8 * ceil_div(B, 8)), block(kThreads);
     auto kern = attention_seq_x32_kernel<D, RP, FUSED>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -673,12 +690,10 @@ hipError_t launch_d(const void* Q, const float* S, const float* V, const void* P
 }  // namespace
 
 bool attention_seq_x32_supported(int d, int r) {
-    return (d == 64 || d == 128 || d == 256) && r >= 4 && r <= 64 && (r % 4) == 0;
+    return (d == 64 || d == 128 || d == 256) && r >= 4 && r <= (d == 256 ? 32 : 64) && (r % 4) == 0;
 }
 
-bool attention_seq_x32_from_x_supported(int d, int r) {
-    return attention_seq_x32_supported(d, r) && (r <= 32 || d <= 128);
-}
+bool attention_seq_x32_from_x_supported(int d, int r) { return attention_seq_x32_supported(d, r); }
 
 // Q is bf16; S must not be null.
 hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* V, const float* P,
@@ -695,8 +710,7 @@ hipError_t launch_attention_seq_x32(const void* Q, const float* S, const float* 
     switch (d) {
         case 64: return launch_d<64, 64, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
         case 128: return launch_d<128, 64, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
-        case 256: return launch_d<256, 64, false>(Q, S, V, P, lengths, B, N, r, M, scale, O, stream);
-        default: return hipErrorInvalidValue;
+        default: return hipErrorInvalidValue;   // d = 256 takes ranks up to 32
     }
 }
 
