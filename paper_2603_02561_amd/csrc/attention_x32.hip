@@ -57,8 +57,7 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kQW = 32;              // queries per wave
 constexpr int kNT = 128;             // rows of P per tile
 constexpr int kNB = kNT / 32;        // blocks per tile
-// RP is the padded rank (32 or 64): LDV = RP + 1 floats per row of the V image [D][LDV],
-// LDR = RP + 8 fp16 elements per row of a tile image [kNT][LDR]
+// RP is the padded rank (32 or 64); LDR = RP + 8 fp16 elements per row of a tile image [kNT][LDR]
 constexpr float kLog2e = 1.4426950408889634f;
 // a score more than kShift (in log2 units) above the reference moves the reference there, so
 // no weight exceeds 2^kShift: far inside the fp16 range, and the row sums stay far inside float
