@@ -242,6 +242,38 @@ def main() -> int:
     total_ms = start.elapsed_time(stop)
     ncalls, phase_ms = binding.solar_phase_timing_end()
     attn_ms = sum(a.elapsed_time(b) for a, b in attn_ev) / args.steps
+
+    # The same throughput pass with the projection A3 formed inside the attention kernel
+    # (solar_svd_attention_from_x: P is never stored).  Reported beside `value`, which stays the
+    # path that writes P as solar_svd_factorize's output.
+    fused = None
+    if (not args.from_x and bf16 and w.r % 4 == 0 and w.r <= (32 if w.d == 256 else 64)):
+        def fstep(i):
+            db = sets[i % n_sets]
+            with torch.cuda.stream(streams[i % n_streams]):
+                db.factorize_no_p()
+                db.attention_from_x(scale)
+        for i in range(min(args.warmup, 10)):
+            fstep(i)
+        torch.cuda.synchronize()
+        f0 = torch.cuda.Event(enable_timing=True)
+        f1 = torch.cuda.Event(enable_timing=True)
+        f0.record()
+        for st in streams:
+            st.wait_stream(torch.cuda.current_stream())
+        for i in range(args.steps):
+            fstep(i)
+        for st in streams:
+            torch.cuda.current_stream().wait_stream(st)
+        f1.record()
+        torch.cuda.synchronize()
+        fms = f0.elapsed_time(f1) / args.steps
+        fused = {"value": w.B / (fms * 1e-3), "unit": "user-sequences/s", "ms_per_step": fms,
+                 "note": "same pass through solar_svd_factorize(P = NULL) + solar_svd_attention_from_x"}
+        # leave the buffer sets as the stored-P path left them for the accuracy check below
+        for i in range(n_sets):
+            step(i)
+        torch.cuda.synchronize()
     gram_ms, eig_ms, proj_ms = [p / max(ncalls, 1) for p in phase_ms]
     ms_per_step = total_ms / args.steps
     info_bad = int((sets[0].info != 0).sum().item())
@@ -316,6 +348,7 @@ def main() -> int:
                    "recipe": w.recipe, "buffer_sets": n_sets},
         "phase_ms": phases, "dominant_kernel": dominant, "kernels": kernels,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
+        "fused_projection": fused,
         "streams": n_streams, "serial_pass_ms": solo,
         "value_serial": w.B / (solo["step"] * 1e-3),
         "users_not_converged": info_bad,
