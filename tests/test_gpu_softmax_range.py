@@ -98,3 +98,31 @@ def test_guarded_pass_alone(lib, oracle, r):
             out[(scale, guarded)] = got
         # the two passes round the weights differently but compute the same thing
         assert rel_err(out[(scale, True)], out[(scale, False)]) < 2e-3
+
+
+@pytest.mark.parametrize("r", [32, 64])
+@pytest.mark.parametrize("factor", [2.0 ** -10, 2.0 ** 9])
+def test_input_magnitudes(lib, oracle, r, factor):
+    """Sequences a thousand times smaller and five hundred times larger than the usual ones: the
+    largest singular value then lies outside the range in which the bf16 attention kernel rounds
+    P to 16 bits as it is, and the kernel scales P by 1/S[0] first (and the output back)."""
+    import torch
+    print(f"[case] input magnitude x{factor:g} r={r}", flush=True)
+    w = synth.make_workload("t", 2, 700, 128, r, 150, synth.BF16, "spectrum", 1.0, 0.005, seed=611)
+    X = (w.X * np.float32(factor)).astype(np.float32)     # a power of two: still bf16 values
+    f = oracle.svd_factorize(X, r, w.lengths)
+    assert not (1.0 <= f["S"][0][0] <= 8192.0)
+    db = lib.DeviceBatch(X, w.Q, w.lengths, r, True)
+    db.factorize()
+    torch.cuda.synchronize()
+    assert np.all(db.info.cpu().numpy() == 0)
+    for scale in (1.0 / factor, w.sharp_scale / factor):
+        want = oracle.svd_attention(w.Q, X, f["S"], f["V"], scale, 0, w.lengths)
+        db.attention(scale, 0)
+        torch.cuda.synchronize()
+        err = rel_err(db.O.cpu().numpy().astype(np.float64), want)
+        db.attention_from_x(scale)
+        torch.cuda.synchronize()
+        err_fx = rel_err(db.O.cpu().numpy().astype(np.float64), want)
+        print(f"  scale={scale:.3g} err {err:.3e} fused {err_fx:.3e}", flush=True)
+        assert err < 2e-2 and err_fx < 2e-2
