@@ -55,6 +55,9 @@ def sweep_cases():
         (64, 64, 129, 20, 2, synth.BF16, False),
         (256, 28, 330, 40, 2, synth.BF16, True),
         (256, 32, 128, 257, 1, synth.BF16, False),
+        # bf16 inputs with ranks that are not a multiple of 4 (float attention kernel on bf16 queries)
+        (128, 10, 150, 40, 2, synth.BF16, True),
+        (64, 7, 90, 30, 1, synth.BF16, False),
         # float inputs with ranks that are not a multiple of 4
         (64, 5, 97, 19, 2, synth.F32, True),
         (128, 23, 260, 50, 2, synth.F32, False),
