@@ -286,3 +286,28 @@ def test_edge_shapes(lib, oracle, name, B, N, d, r, M, dtype, lengths):
             assert rel_err(db.O.cpu().numpy(), dense) < tol
     s_err = np.abs(db.S.cpu().numpy() - f["S"]).max() / f["S"].max()
     assert s_err < (1e-4 if dtype == synth.F32 else 1e-3)
+
+
+def test_iteration_cap_is_reported_per_user(lib):
+    """Failure handling forced from the host: with the cap on power steps set to one (a debugging
+    switch of the library) a slowly decaying spectrum fails its first residual check, the kernel
+    ends normally, every user is reported through info (> 0 = steps taken) and the factors it
+    leaves are finite; without the cap the same batch converges."""
+    import os
+    import torch
+    w = synth.make_workload("t", 3, 600, 128, 32, 16, synth.BF16, "spectrum", 0.5, 0.05, seed=777)
+    db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, True)
+    os.environ["SOLAR_EIG_MAXIT"] = "1"
+    try:
+        print("[case] iteration cap 1", flush=True)
+        db.factorize()
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("SOLAR_EIG_MAXIT", None)
+    info = db.info.cpu().numpy()
+    print(f"  info {info.tolist()}", flush=True)
+    assert np.all(info > 0)
+    assert bool(torch.isfinite(db.S).all()) and bool(torch.isfinite(db.V).all())
+    db.factorize()
+    torch.cuda.synchronize()
+    assert np.all(db.info.cpu().numpy() == 0)
