@@ -46,7 +46,8 @@ typedef enum {
     SOLAR_ERR_INVALID_ARG = 1,
     SOLAR_ERR_UNSUPPORTED = 2,
     SOLAR_ERR_WORKSPACE = 3,
-    SOLAR_ERR_HIP = 4
+    SOLAR_ERR_HIP = 4,
+    SOLAR_ERR_SCRATCH_LIMIT = 6   /* solar_svd_factorize_static only: see SOLAR_STATIC_SCRATCH_BYTES */
 } solar_status;
 
 typedef enum { SOLAR_F32 = 0, SOLAR_BF16 = 1 } solar_dtype;
@@ -97,6 +98,30 @@ solar_status solar_svd_factorize(const void* X, const int32_t* lengths, int B, i
                                  int r, solar_dtype t, float* S, float* V, float* P,
                                  int32_t* info, void* workspace, size_t workspace_bytes,
                                  void* stream);
+
+/*
+ * solar_svd_factorize for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The same kernels run with their scratch (the split-N partial blocks of the Gram contraction
+ * and G) in an array built into the library's device code, SOLAR_STATIC_SCRATCH_BYTES long;
+ * every device the library is used on holds one copy of it until the process ends.  The call
+ * allocates and frees nothing, on the device or through any library.  The array's device address
+ * is looked up on the first call made with a given device current; the stream must belong to the
+ * current device.
+ *   - Arguments, outputs, info and return codes as for solar_svd_factorize, minus the workspace.
+ *   - Sizes for which solar_workspace_bytes(B, N, d, r, 0, t) exceeds SOLAR_STATIC_SCRATCH_BYTES
+ *     return SOLAR_ERR_SCRATCH_LIMIT; nothing is launched.  (The five benchmark workloads need
+ *     0.1 to 42 MB.)
+ *   - All calls on one device share that device's array, and it keeps the last call's contents.
+ *     Nothing in it has to start at zero (every partial block and G is written before it is
+ *     read), so nothing is cleared.  Calls whose work overlaps in time on one device (different
+ *     streams, or several host threads) race on it: order them on one stream or with events.
+ *   - Per-phase timing (solar_phase_timing_begin) does not cover this call.
+ */
+#define SOLAR_STATIC_SCRATCH_BYTES (48u * 1024u * 1024u)
+solar_status solar_svd_factorize_static(const void* X, const int32_t* lengths, int B, int N, int d,
+                                        int r, solar_dtype t, float* S, float* V, float* P,
+                                        int32_t* info, void* stream);
 
 /*
  * Attention step, Attn_SVD = MatMul(MatMul(Query, Key_r^T), Value_r) with

@@ -15,6 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsolar.so")
 
 SOLAR_OK = 0
+SOLAR_ERR_SCRATCH_LIMIT = 6
+SOLAR_STATIC_SCRATCH_BYTES = 48 * 1024 * 1024
 SOLAR_F32 = 0
 SOLAR_BF16 = 1
 SOLAR_ATTN_SEQ_SOFTMAX = 0
@@ -37,6 +39,8 @@ _lib.solar_gram.restype = _ci
 _lib.solar_svd_factorize.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _vp, _vp, _vp,
                                      _sz, _vp]
 _lib.solar_svd_factorize.restype = _ci
+_lib.solar_svd_factorize_static.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _vp, _vp, _vp]
+_lib.solar_svd_factorize_static.restype = _ci
 _lib.solar_svd_attention.argtypes = [_vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _cf, _ci,
                                      _ci, _vp, _vp, _sz, _vp]
 _lib.solar_svd_attention.restype = _ci
@@ -127,6 +131,17 @@ def solar_svd_factorize(X, lengths, r: int, S, V, P, info, workspace,
     rc = _lib.solar_svd_factorize(_ptr(X), _ptr(lengths), B, N, d, int(r), _dtype_code(X), _ptr(S),
                                   _ptr(V), _ptr(P), _ptr(info), _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream())
+    if rc != SOLAR_OK and raise_on_error:
+        raise SolarError(rc)
+    return rc
+
+
+def solar_svd_factorize_static(X, lengths, r: int, S, V, P, info, raise_on_error: bool = True) -> int:
+    """solar_svd_factorize with the library's built-in scratch array instead of a workspace."""
+    _check(X, lengths, S, V, P, info)
+    B, N, d = X.shape
+    rc = _lib.solar_svd_factorize_static(_ptr(X), _ptr(lengths), B, N, d, int(r), _dtype_code(X), _ptr(S),
+                                         _ptr(V), _ptr(P), _ptr(info), _stream())
     if rc != SOLAR_OK and raise_on_error:
         raise SolarError(rc)
     return rc

@@ -3,8 +3,15 @@
 #include "../../include/solar.h"
 
 #include <cstdlib>
+#include <mutex>
 
 #include "kernels.h"
+
+// Scratch of solar_svd_factorize_static: the split-N partial blocks of the Gram contraction and
+// G, which the other entry point takes from the caller's workspace.  Every device the library
+// runs on holds its own copy until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress; the device address it yields is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[SOLAR_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -68,6 +75,67 @@ EigParams eig_params_from_env() {
     return p;
 }
 
+solar_status factorize_check(const void* X, int B, int N, int d, int r, solar_dtype t, const float* S,
+                             const float* V) {
+    if (!X || !S || !V || B <= 0 || N <= 0 || d <= 0 || r <= 0) return SOLAR_ERR_INVALID_ARG;
+    if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
+    if (r > d || r > N) return SOLAR_ERR_INVALID_ARG;
+    if (!supported_shape(d, r)) return SOLAR_ERR_UNSUPPORTED;
+    return SOLAR_OK;
+}
+
+// The three phases of the factorization on `st`, with `ws` (validated by the caller) as the
+// scratch for the split-N partial blocks and G.
+solar_status factorize_enqueue(const void* X, const int32_t* lengths, int B, int N, int d, int r, solar_dtype t,
+                               float* S, float* V, float* P, int32_t* info, void* ws, bool timed,
+                               hipStream_t st) {
+    Carve c = carve(ws, B, N, d);
+    const bool bf16 = t == SOLAR_BF16;
+    const int call = g_timer.calls;
+    if (timed) timer_mark(call, 0, st);
+    // where the eigen-iteration can sum the split-N partial blocks itself, G is never formed
+    const bool fused = gram_partials_consumable(d) && !std::getenv("SOLAR_GRAM_FINALIZE");
+    hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, !fused, st);
+    if (e != hipSuccess) return SOLAR_ERR_HIP;
+    if (timed) timer_mark(call, 1, st);
+    e = launch_eig(c.G, fused ? c.partials : nullptr, gram_nsplit(B, N), lengths, B, N, d, r, S, V, info,
+                   eig_params_from_env(), st);
+    if (e != hipSuccess) return SOLAR_ERR_HIP;
+    if (timed) timer_mark(call, 2, st);
+    if (P) {
+        e = launch_project(X, lengths, V, info, B, N, d, r, bf16, P, st);
+        if (e != hipSuccess) return SOLAR_ERR_HIP;
+    }
+    if (timed) {
+        timer_mark(call, 3, st);
+        if (g_timer.enabled && call < PhaseTimer::kMaxCalls) g_timer.calls = call + 1;
+    }
+    return SOLAR_OK;
+}
+
+// Device address of the built-in scratch array on the current device.  Every device holds its
+// own copy of the array at its own address, so the address is looked up once per device (on the
+// first call made with that device current) and kept.
+hipError_t static_scratch_of_current_device(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptr_of_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of_device[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p || ((uintptr_t)p & 255)) return hipErrorInvalidSymbol;
+        ptr_of_device[dev] = p;
+    }
+    *out = ptr_of_device[dev];
+    return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -79,6 +147,7 @@ const char* solar_status_string(solar_status s) {
         case SOLAR_ERR_UNSUPPORTED: return "unsupported shape or type";
         case SOLAR_ERR_WORKSPACE: return "workspace too small or misaligned";
         case SOLAR_ERR_HIP: return "HIP launch error";
+        case SOLAR_ERR_SCRATCH_LIMIT: return "sizes need more scratch than the built-in array of the allocation-free call holds";
         default: return "unknown status";
     }
 }
@@ -124,32 +193,23 @@ solar_status solar_gram(const void* X, const int32_t* lengths, int B, int N, int
 solar_status solar_svd_factorize(const void* X, const int32_t* lengths, int B, int N, int d, int r,
                                  solar_dtype t, float* S, float* V, float* P, int32_t* info,
                                  void* workspace, size_t workspace_bytes, void* stream) {
-    if (!X || !S || !V || B <= 0 || N <= 0 || d <= 0 || r <= 0) return SOLAR_ERR_INVALID_ARG;
-    if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
-    if (r > d || r > N) return SOLAR_ERR_INVALID_ARG;
-    if (!supported_shape(d, r)) return SOLAR_ERR_UNSUPPORTED;
-    Carve c = carve(workspace, B, N, d);
-    if (!workspace || workspace_bytes < c.total || ((uintptr_t)workspace & 255)) return SOLAR_ERR_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    const bool bf16 = t == SOLAR_BF16;
-    const int call = g_timer.calls;
-    timer_mark(call, 0, st);
-    // where the eigen-iteration can sum the split-N partial blocks itself, G is never formed
-    const bool fused = gram_partials_consumable(d) && !std::getenv("SOLAR_GRAM_FINALIZE");
-    hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, !fused, st);
-    if (e != hipSuccess) return SOLAR_ERR_HIP;
-    timer_mark(call, 1, st);
-    e = launch_eig(c.G, fused ? c.partials : nullptr, gram_nsplit(B, N), lengths, B, N, d, r, S, V, info,
-                   eig_params_from_env(), st);
-    if (e != hipSuccess) return SOLAR_ERR_HIP;
-    timer_mark(call, 2, st);
-    if (P) {
-        e = launch_project(X, lengths, V, info, B, N, d, r, bf16, P, st);
-        if (e != hipSuccess) return SOLAR_ERR_HIP;
-    }
-    timer_mark(call, 3, st);
-    if (g_timer.enabled && call < PhaseTimer::kMaxCalls) g_timer.calls = call + 1;
-    return SOLAR_OK;
+    const solar_status v = factorize_check(X, B, N, d, r, t, S, V);
+    if (v != SOLAR_OK) return v;
+    if (!workspace || workspace_bytes < carve(nullptr, B, N, d).total || ((uintptr_t)workspace & 255))
+        return SOLAR_ERR_WORKSPACE;
+    return factorize_enqueue(X, lengths, B, N, d, r, t, S, V, P, info, workspace, true, (hipStream_t)stream);
+}
+
+solar_status solar_svd_factorize_static(const void* X, const int32_t* lengths, int B, int N, int d, int r,
+                                        solar_dtype t, float* S, float* V, float* P, int32_t* info,
+                                        void* stream) {
+    const solar_status v = factorize_check(X, B, N, d, r, t, S, V);
+    if (v != SOLAR_OK) return v;
+    if (carve(nullptr, B, N, d).total > (size_t)SOLAR_STATIC_SCRATCH_BYTES) return SOLAR_ERR_SCRATCH_LIMIT;
+    void* ws = nullptr;
+    if (static_scratch_of_current_device(&ws) != hipSuccess) return SOLAR_ERR_HIP;
+    // no phase timing here: its events are created on demand, which allocates
+    return factorize_enqueue(X, lengths, B, N, d, r, t, S, V, P, info, ws, false, (hipStream_t)stream);
 }
 
 size_t solar_rsvd_workspace_bytes(int B, int N, int d, int r) {

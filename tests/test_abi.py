@@ -68,6 +68,13 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert lib.solar_svd_factorize(fake, None, 1, 640, 64, 8, 0, fake, fake, None, None, None, 0, None) == WORKSPACE
     assert lib.solar_svd_factorize(fake, None, 1, 640, 64, 8, 0, fake, fake, None, None, fake, 16, None) == WORKSPACE
     assert lib.solar_svd_factorize(fake, None, 1, 640, 64, 8, 0, fake, fake, None, None, 0x1010, 1 << 30, None) == WORKSPACE
+    # the allocation-free variant: same checks, and sizes beyond its built-in scratch array
+    lib.solar_svd_factorize_static.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp]
+    lib.solar_svd_factorize_static.restype = ci
+    SCRATCH_LIMIT = 6
+    assert lib.solar_svd_factorize_static(None, None, 1, 64, 64, 8, 0, fake, fake, None, None, None) == INVALID
+    assert lib.solar_svd_factorize_static(fake, None, 1, 640, 96, 8, 0, fake, fake, None, None, None) == UNSUPPORTED
+    assert lib.solar_svd_factorize_static(fake, None, 64, 100000, 256, 32, 1, fake, fake, None, None, None) == SCRATCH_LIMIT
     lib.solar_svd_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, cf, ci, ci, vp, vp, sz, vp]
     lib.solar_svd_attention.restype = ci
     assert lib.solar_svd_attention(fake, fake, fake, None, None, 1, 64, 64, 8, 4, 1.0, 0, 0, fake, None, 0, None) == INVALID
