@@ -154,20 +154,47 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         if (rescale) { pscale = 1.f / s0; punscale = s0; }
     }
 
+    // The loads of the prologue are issued before anything waits: the wave's queries (HBM), then
+    // this thread's share of V; the tile buffers are zeroed while they are in flight.
+    constexpr int KQ = D / 16;            // 16-column steps of the query product
+    const int m = m_wave + n32;
+    const bool valid = m < M;
+    v4u qreg[KQ];
+    {
+        const uint16_t* qrow = reinterpret_cast<const uint16_t*>(Qv) + ((size_t)b * M + (valid ? m : 0)) * D + 8 * h;
+#pragma unroll
+        for (int kk = 0; kk < KQ; ++kk) qreg[kk] = *reinterpret_cast<const v4u*>(qrow + 16 * kk);
+    }
+    // V by rank quads (r is a multiple of 4): quad e of the D * RP / 4 is row e / (RP/4), ranks
+    // 4 * (e % (RP/4)) .. +3; consecutive threads read consecutive quads of a row
+    constexpr int VQ = D * (RP / 4) / kThreads;   // quads per thread
+    static_assert(VQ * kThreads == D * (RP / 4), "whole quads per thread");
+    v4f vreg[VQ];
+#pragma unroll
+    for (int i = 0; i < VQ; ++i) {
+        const int e = tid + i * kThreads, k = e / (RP / 4), c4 = e % (RP / 4);
+        vreg[i] = 4 * c4 < r ? *reinterpret_cast<const v4f*>(V + ((size_t)b * D + k) * r + 4 * c4) : v4f{0.f, 0.f, 0.f, 0.f};
+    }
     // zero the tile buffers once: padded rank columns stay zero for ever
-    for (int e = tid; e < 3 * kBuf / 2; e += kThreads) reinterpret_cast<uint32_t*>(tiles)[e] = 0u;
+    static_assert((3 * kBuf) % 8 == 0, "whole 16-byte stores");
+    for (int e = tid; e < 3 * kBuf / 8; e += kThreads) reinterpret_cast<v4u*>(tiles)[e] = v4u{0u, 0u, 0u, 0u};
     if (tid == 0) *redo = 0;
-    for (int e = tid; e < D * RP; e += kThreads) {
-        const int k = e / RP, c = e % RP;   // consecutive threads read consecutive ranks of a row of V
-        const float v = (c < r) ? V[((size_t)b * D + k) * r + c] : 0.f;
-        const uint32_t hi = __float_as_uint(v) & 0xffff0000u;
-        const float rem = v - __uint_as_float(hi);
-        const uint32_t lo = (__float_as_uint(rem) + 0x7fffu + ((__float_as_uint(rem) >> 16) & 1u)) >> 16;
-        vt[c * LDVT + k] = (uint16_t)(hi >> 16);
-        vt[(RP + c) * LDVT + k] = (uint16_t)lo;
-        const int pos = 4 * quad_pos(c >> 2) + (c & 3);
-        vimg[k * LDI + pos] = (uint16_t)(hi >> 16);
-        vimg[(D + k) * LDI + pos] = (uint16_t)lo;
+#pragma unroll
+    for (int i = 0; i < VQ; ++i) {
+        const int e = tid + i * kThreads, k = e / (RP / 4), c4 = e % (RP / 4);
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float v = vreg[i][u];
+            hi[u] = __float_as_uint(v) & 0xffff0000u;
+            const float rem = v - __uint_as_float(hi[u]);
+            lo[u] = (__float_as_uint(rem) + 0x7fffu + ((__float_as_uint(rem) >> 16) & 1u)) >> 16;
+            vt[(4 * c4 + u) * LDVT + k] = (uint16_t)(hi[u] >> 16);
+            vt[(RP + 4 * c4 + u) * LDVT + k] = (uint16_t)lo[u];
+        }
+        const int pos = 4 * quad_pos(c4);
+        *reinterpret_cast<uint2*>(vimg + k * LDI + pos) = uint2{(hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]};
+        *reinterpret_cast<uint2*>(vimg + (D + k) * LDI + pos) = uint2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
     }
     __syncthreads();
 
@@ -181,13 +208,10 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         for (int hh = 0; hh < NH; ++hh)
 #pragma unroll
             for (int t = 0; t < 16; ++t) qt[hh][t] = 0.f;
-        const int m = m_wave + n32;
-        const bool valid = m < M;
-        const uint16_t* qrow = reinterpret_cast<const uint16_t*>(Qv) + ((size_t)b * M + (valid ? m : 0)) * D + 8 * h;
         const uint16_t* va = vt + n32 * LDVT + 8 * h;
-#pragma unroll 4
-        for (int kk = 0; kk < D / 16; ++kk) {
-            v4u w = *reinterpret_cast<const v4u*>(qrow + 16 * kk);
+#pragma unroll
+        for (int kk = 0; kk < KQ; ++kk) {
+            v4u w = qreg[kk];
             if (!valid) w = v4u{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int hh = 0; hh < NH; ++hh) {
@@ -233,10 +257,12 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
                          (FUSED ? (size_t)b * N * (2u * D) + (size_t)fx_g * (D / 2) : (size_t)b * N * (4u * r));
     const uint32_t ld_off0 = FUSED ? (uint32_t)fx_row * row_bytes : (uint32_t)(RPT * ld_np) * row_bytes + ld_col;
     uint32_t ld_off = ld_off0;   // this thread's first row of the next tile to fetch
-    // two sets of staging registers: a tile is loaded two loop iterations before it is converted,
-    // so that the loads (L2 or HBM) have a whole tile of arithmetic to arrive
-    v4f stage[2][RPT];
-    v4u xst[2][FUSED ? KS : 1];
+    // NST sets of staging registers: a tile is loaded NST - 1/2 loop iterations before it is
+    // converted, so that the loads (L2 or HBM) have more than a tile of arithmetic to arrive;
+    // three sets where the registers allow it (4 % fewer cycles than two at r <= 32)
+    constexpr int NST = (FUSED || RP == 64) ? 2 : 3;
+    v4f stage[NST][RPT];
+    v4u xst[NST][FUSED ? KS : 1];
     auto fetch = [&](int tile, auto par_tag) __attribute__((always_inline)) {
         constexpr int par = decltype(par_tag)::value;
         if constexpr (FUSED) {
@@ -387,8 +413,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // behind the exponentials of the group after, and the matrix instructions are spread
     // between the groups so that each finds the matrix pipe free.
     // sa_next and za_this point at the score operands of block j+2 and the Z operands of block j.
-    // Every MFMA is issued at raised wave priority, so that the matrix unit is fed ahead of the
-    // other wave's vector work.
+    // (Raising the wave priority around every MFMA cost 4 % of the loop's cycles for the twelve
+    // extra scalar instructions per slot; the oldest-first arbitration feeds the matrix unit as well.)
 #define SOLAR_FENCE __builtin_amdgcn_sched_barrier(0)
     auto slot = [&](int j, auto cur_tag, auto guard_tag, const uint16_t* sa_next, const uint16_t* za_this)
                     __attribute__((always_inline)) {
@@ -413,9 +439,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
         };
         if constexpr (RP == 32) {
             SOLAR_FENCE;
-            __builtin_amdgcn_s_setprio(1);
+            
             s[nxt] = mma32(sA[nxt][0], qB[0], cinit);
-            __builtin_amdgcn_s_setprio(0);
+            
             SOLAR_FENCE;
             E(0); sA[cur][0] = *reinterpret_cast<const v4u*>(sa_next);
             SOLAR_FENCE;
@@ -426,9 +452,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             SOLAR_FENCE;
             E(3); zhi = lds_read_tr16(za_this + 8 * LDR);
             SOLAR_FENCE;
-            __builtin_amdgcn_s_setprio(1);
+            
             s[nxt] = mma32(sA[nxt][1], qB[1], s[nxt]);
-            __builtin_amdgcn_s_setprio(0);
+            
             SOLAR_FENCE;
             E(4); C(0);
             SOLAR_FENCE;
@@ -438,9 +464,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             SOLAR_FENCE;
             E(7);
             SOLAR_FENCE;
-            __builtin_amdgcn_s_setprio(1);
+            
             z[0] = mma32(zA[nxt][0][0], wp[nxt][0], z[0]);
-            __builtin_amdgcn_s_setprio(0);
+            
             SOLAR_FENCE;
             zA[cur][0][0] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
             E(8); C(2);
@@ -451,13 +477,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             SOLAR_FENCE;
             E(11);
             SOLAR_FENCE;
-            __builtin_amdgcn_s_setprio(1);
+            
             z[0] = mma32(zA[nxt][0][1], wp[nxt][1], z[0]);
-            __builtin_amdgcn_s_setprio(0);
+            
             SOLAR_FENCE;
-            __builtin_amdgcn_s_setprio(1);
+            
             lacc = mma16(ones, wp[cur][0], lacc);
-            __builtin_amdgcn_s_setprio(0);
+            
             SOLAR_FENCE;
             E(12); zlo = lds_read_tr16(za_this + 16 * LDR);
             SOLAR_FENCE;
@@ -470,16 +496,16 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             C(6); C(7);
             zA[cur][0][1] = v4u{zlo.x, zlo.y, zhi.x, zhi.y};
             SOLAR_FENCE;
-            __builtin_amdgcn_s_setprio(1);
+            
             lacc = mma16(ones, wp[cur][1], lacc);
-            __builtin_amdgcn_s_setprio(0);
+            
             SOLAR_FENCE;
             X(2); X(3);
             SOLAR_FENCE;
         } else {
             // two rank halves: four score products and four Z products per block; the matrix unit
             // is then as busy as the vector ALU's issue port, so its instructions are spread evenly
-#define SOLAR_MFMA(stmt) SOLAR_FENCE; __builtin_amdgcn_s_setprio(1); stmt; __builtin_amdgcn_s_setprio(0); SOLAR_FENCE
+#define SOLAR_MFMA(stmt) SOLAR_FENCE;  stmt;  SOLAR_FENCE
             uint2 t0, t1, t2, t3;
             SOLAR_MFMA(s[nxt] = mma32(sA[nxt][0], qB[0], cinit));
             E(0); sA[cur][0] = *reinterpret_cast<const v4u*>(sa_next);
@@ -544,7 +570,8 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     reset_state();
     if (ntiles > 0) { fetch(0, tag0{}); commit(tiles, 0, tag0{}); }
     if (ntiles > 1) { fetch(1, tag0{}); commit(tiles + kBuf, 1, tag0{}); }
-    fetch(2, tag0{});
+    fetch(2, std::integral_constant<int, 2 % NST>{});
+    if constexpr (NST == 3) fetch(3, tag0{});
     __syncthreads();
     if (nblocks > 0) {
         // S(0) and the reference of the first block; the score operands of block 1
@@ -564,32 +591,35 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // byte-free rotation of the three tile buffers: element offsets of the tile being
     // multiplied, the next one and the one being converted
     int o_cur = 0, o_nxt = kBuf, o_wr = 2 * kBuf;
-    // one tile: its four slots, the loads of tile + 3 into the staging set of the other parity and,
-    // half way, the conversion of tile + 2 (loaded an iteration ago) into the free buffer
+    // one tile: its four slots, the loads of tile + 1 + NST into the staging set that the
+    // conversion of the tile before freed and, half way, the conversion of tile + 2 (loaded
+    // NST - 1 iterations ago) into the free buffer
     auto run_tile = [&](int tile, auto par_tag) __attribute__((always_inline)) {
         constexpr int par = decltype(par_tag)::value;
         // (tiles past the end are loaded from clamped rows and converted into a buffer nobody
         // reads: the loop body stays free of branches around its loads, so the wait before a
         // conversion counts the younger loads instead of draining them)
-        fetch(tile + 3, std::integral_constant<int, par ^ 1>{});
+        fetch(tile + 1 + NST, std::integral_constant<int, (par + 1) % NST>{});
         const uint16_t* sa_cur = tiles + o_cur + sa_off;
         const uint16_t* sa_nxt = tiles + o_nxt + sa_off;
         const uint16_t* za_cur = tiles + o_cur + za_off;
         const int j0 = tile * kNB;
         slot(j0, tag0{}, guard_tag, sa_cur + 2 * 32 * LDR, za_cur);
         if (__builtin_expect(j0 + 1 < nblocks, 1)) slot(j0 + 1, tag1{}, guard_tag, sa_cur + 3 * 32 * LDR, za_cur + 32 * LDR);
-        commit(tiles + o_wr, tile + 2, par_tag);
+        commit(tiles + o_wr, tile + 2, std::integral_constant<int, (par + 2) % NST>{});
         if (__builtin_expect(j0 + 2 < nblocks, 1)) slot(j0 + 2, tag0{}, guard_tag, sa_nxt, za_cur + 2 * 32 * LDR);
         if (__builtin_expect(j0 + 3 < nblocks, 1)) slot(j0 + 3, tag1{}, guard_tag, sa_nxt + 32 * LDR, za_cur + 3 * 32 * LDR);
         __syncthreads();
         const int o = o_cur; o_cur = o_nxt; o_nxt = o_wr; o_wr = o;
     };
     int tile = 0;
-    for (; tile + 1 < ntiles; tile += 2) {
+    for (; tile + NST - 1 < ntiles; tile += NST) {
         run_tile(tile, tag0{});
         run_tile(tile + 1, tag1{});
+        if constexpr (NST == 3) run_tile(tile + 2, std::integral_constant<int, 2>{});
     }
     if (tile < ntiles) run_tile(tile, tag0{});
+    if constexpr (NST == 3) { if (tile + 1 < ntiles) run_tile(tile + 1, tag1{}); }
     // Z of the last block trails the loop
     if (nblocks > 0) {
         if ((nblocks - 1) & 1) {
@@ -646,7 +676,6 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
             zh[c] = v4u{hw[0], hw[1], hw[2], hw[3]};
             zl[c] = v4u{lw[0], lw[1], lw[2], lw[3]};
         }
-        const int m = m_wave + n32;
         for (int db = 0; db < D / 32; ++db) {
             v16f o;
 #pragma unroll
