@@ -11,8 +11,9 @@
  *     torch tensor's data_ptr()).  The library never allocates or frees device
  *     memory and never synchronizes: all work is enqueued on `stream`, a
  *     hipStream_t passed as void* (NULL = the default stream).
- *   - Arrays are row-major with the last index contiguous.  B users, N rows per
- *     (padded) sequence, d embedding columns, r rank, M candidates.
+ *   - Arrays are row-major with the last index contiguous and start on a 16-byte
+ *     boundary.  B users, N rows per (padded) sequence, d embedding columns, r rank,
+ *     M candidates.
  *   - `lengths` ([B] int32, device) holds the number of valid rows of each user;
  *     NULL means every user has N valid rows.  Rows at or past the valid length
  *     are never read as data: they are left out of the factorization and masked
@@ -47,6 +48,8 @@ typedef enum {
     SOLAR_ERR_UNSUPPORTED = 2,
     SOLAR_ERR_WORKSPACE = 3,
     SOLAR_ERR_HIP = 4,
+    SOLAR_ERR_NOT_CONVERGED = 5,  /* never returned by the asynchronous calls (they do not wait for
+                                     the device): solar_info_status() derives it from `info` */
     SOLAR_ERR_SCRATCH_LIMIT = 6   /* solar_svd_factorize_static only: see SOLAR_STATIC_SCRATCH_BYTES */
 } solar_status;
 
@@ -66,6 +69,28 @@ typedef enum {
 /* Human-readable name of a status code (static string, host memory). */
 const char* solar_status_string(solar_status s);
 
+/*
+ * Verdict over the per-user `info` array of a factorization, after the caller has waited for
+ * the stream and copied `info` to HOST memory: SOLAR_OK if every entry is 0,
+ * SOLAR_ERR_INVALID_ARG if any entry is negative (a bad length), else
+ * SOLAR_ERR_NOT_CONVERGED (some user's eigen-iteration reached its cap; that user's factors
+ * are the best available and finite).
+ */
+solar_status solar_info_status(const int32_t* info_host, int B);
+
+/*
+ * Debug switches, process-wide, for tests that must reach a rarely taken path from the host
+ * without an input built to provoke it.  Not for production use; both are off (0) at start.
+ *   SOLAR_DEBUG_EIG_MAX_ITER        value > 0 caps the power steps of the eigen-iteration in
+ *                                   solar_svd_factorize (users that hit the cap report it in
+ *                                   `info`); 0 restores the default cap of 40
+ *   SOLAR_DEBUG_FORCE_GUARDED_PASS  nonzero makes the fp16 attention kernel of mode 0 skip its
+ *                                   optimistic pass and walk the sequence with the guarded pass
+ *                                   (the one that moves the softmax reference) straight away
+ */
+typedef enum { SOLAR_DEBUG_EIG_MAX_ITER = 0, SOLAR_DEBUG_FORCE_GUARDED_PASS = 1 } solar_debug_key;
+solar_status solar_debug_option(solar_debug_key key, int value);
+
 /* Bytes of device scratch that any of the calls below needs for these sizes. */
 size_t solar_workspace_bytes(int B, int N, int d, int r, int M, solar_dtype t);
 
@@ -77,16 +102,24 @@ size_t solar_workspace_bytes(int B, int N, int d, int r, int M, solar_dtype t);
  * The power iteration Omega <- X^T (X Omega) of Algorithm 1 is applied through
  * the Gram matrix G = X^T X, formed in one pass over X; the subspace iteration
  * and the small decomposition then run on G, one workgroup per user.  U is never
- * formed ("we eliminate U"); instead the projection P = X V (= U S) is returned.
+ * formed (Section "SVD-Attention" eliminates it from Key^T Value); the projection
+ * P = X V (= U S) is returned instead.
  *
  *   X        in  [B,N,d] of type t
  *   lengths  in  [B] or NULL
  *   S        out [B,r]   singular values, descending
  *   V        out [B,d,r] right singular vectors; each column's largest-magnitude
- *                        entry is positive.  Components whose singular value is
- *                        below about 3e-3 of the largest cannot be resolved
- *                        through a float Gram matrix: they come back as S = 0 with
- *                        a zero column of V.
+ *                        entry is positive.
+ *                        Resolution: the factors come from the float Gram matrix, whose
+ *                        eigenvalues are the squared singular values, so the direction
+ *                        of component k is resolved to about 2^-24 (s_1/s_k)^2 (7e-5
+ *                        at s_k = 5e-3 s_1); S and the attention outputs stay within
+ *                        the 1e-4 contract of the float path for every component that
+ *                        is returned.  A component below 3.2e-3 of s_1 (1e-5 of the
+ *                        largest eigenvalue of G) is treated as rank deficiency: it
+ *                        comes back as S = 0 with a zero column of V, which is how
+ *                        the caller sees that it was dropped; the 1e-4 contract then
+ *                        holds against the factorization without it.
  *   P        out [B,N,r] = X V, rows at or past the valid length are zero; may be
  *                        NULL if only modes 1 and 2 or solar_svd_attention_from_x
  *                        will be used
@@ -201,7 +234,7 @@ solar_status solar_apply_weights(const void* In, const float* W, int rows, int d
  * sym(A) = (A + A^T)/2, F_ij = 1/(s_j^2 - s_i^2) for i != j (the orientation confirmed by finite
  * differences; the printed F is its transpose), F_ij = 0 on the diagonal and wherever
  * |s_i^2 - s_j^2| <= gap_rel * s_1^2 (the paper states no guard; pass 0 for none).  Only the part
- * of V_bar inside span(V) contributes ("within truncated subspace").
+ * of V_bar inside span(V) contributes (the truncated form of "Backward Pass Through SVD").
  *   S, V, P        from solar_svd_factorize (P is required)
  *   S_bar  in  [B,r]      dL/dS          V_bar  in  [B,d,r]   dL/dV
  *   dX     out [B,N,d] float; rows >= lengths[b] are zero

@@ -15,7 +15,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsolar.so")
 
 SOLAR_OK = 0
+SOLAR_ERR_NOT_CONVERGED = 5
 SOLAR_ERR_SCRATCH_LIMIT = 6
+SOLAR_DEBUG_EIG_MAX_ITER = 0
+SOLAR_DEBUG_FORCE_GUARDED_PASS = 1
 SOLAR_STATIC_SCRATCH_BYTES = 48 * 1024 * 1024
 SOLAR_F32 = 0
 SOLAR_BF16 = 1
@@ -61,6 +64,10 @@ _lib.solar_apply_weights.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp]
 _lib.solar_apply_weights.restype = _ci
 _lib.solar_svd_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _cf, _vp, _vp, _sz, _vp]
 _lib.solar_svd_backward.restype = _ci
+_lib.solar_info_status.argtypes = [_vp, _ci]
+_lib.solar_info_status.restype = _ci
+_lib.solar_debug_option.argtypes = [_ci, _ci]
+_lib.solar_debug_option.restype = _ci
 _lib.solar_phase_timing_begin.argtypes = []
 _lib.solar_phase_timing_begin.restype = None
 _lib.solar_phase_timing_end.argtypes = [ctypes.POINTER(ctypes.c_float)]
@@ -101,6 +108,16 @@ def solar_status_string(code: int) -> str:
 
 def solar_workspace_bytes(B: int, N: int, d: int, r: int, M: int, dtype_code: int) -> int:
     return int(_lib.solar_workspace_bytes(B, N, d, r, M, dtype_code))
+
+
+def solar_info_status(info) -> int:
+    """Status over a factorization's per-user info (waits for the device and copies it to the host)."""
+    host = info.detach().to("cpu", torch.int32).contiguous()
+    return int(_lib.solar_info_status(ctypes.c_void_p(host.data_ptr()), host.numel()))
+
+
+def solar_debug_option(key: int, value: int) -> int:
+    return int(_lib.solar_debug_option(int(key), int(value)))
 
 
 def solar_phase_timing_begin() -> None:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsolar.so")
-SOURCES = ["api", "gram", "eig", "project", "rsvd", "attention", "attention_bf16", "attention_x32", "linear", "backward", "dense_ref"]
+SOURCES = ["api", "gram", "eig", "project", "rsvd", "attention", "attention_x32", "linear", "backward", "dense_ref"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

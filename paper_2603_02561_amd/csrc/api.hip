@@ -2,8 +2,10 @@
 // carving and kernel launches on the caller's stream.  See include/solar.h.
 #include "../../include/solar.h"
 
-#include <cstdlib>
+#include <atomic>
+#include <map>
 #include <mutex>
+#include <utility>
 
 #include "kernels.h"
 
@@ -63,17 +65,19 @@ void timer_mark(int call, int slot, hipStream_t st) {
     (void)hipEventRecord(g_timer.ev[call][slot], st);
 }
 
-EigParams eig_params_from_env() {
+// Debug switches (solar_debug_option); both default to off.
+std::atomic<int> g_debug_eig_max_iter{0};
+std::atomic<int> g_debug_force_guarded{0};
+
+EigParams eig_params() {
     EigParams p = eig_default_params();
-    // Debug overrides for tuning the eigen-iteration without a rebuild.
-    if (const char* s = std::getenv("SOLAR_EIG_TOL")) p.tol_res = (float)std::atof(s);
-    if (const char* s = std::getenv("SOLAR_EIG_ORTH")) p.tol_orth = (float)std::atof(s);
-    if (const char* s = std::getenv("SOLAR_EIG_SWEEPS")) p.sweeps = std::atoi(s);
-    if (const char* s = std::getenv("SOLAR_EIG_MAXIT")) p.max_iter = std::atoi(s);
-    if (const char* s = std::getenv("SOLAR_EIG_DEBUG")) p.debug_counts = std::atoi(s);
-    if (const char* s = std::getenv("SOLAR_EIG_MGS")) p.mgs_steps = std::atoi(s);
+    const int cap = g_debug_eig_max_iter.load(std::memory_order_relaxed);
+    if (cap > 0) p.max_iter = cap;
     return p;
 }
+
+// a byte offset into one user's rows must fit the 32 bits the attention kernels keep it in
+bool rows_fit_32bit(int N, size_t row_bytes) { return (size_t)N * row_bytes < ((size_t)1 << 32); }
 
 solar_status factorize_check(const void* X, int B, int N, int d, int r, solar_dtype t, const float* S,
                              const float* V) {
@@ -94,12 +98,12 @@ solar_status factorize_enqueue(const void* X, const int32_t* lengths, int B, int
     const int call = g_timer.calls;
     if (timed) timer_mark(call, 0, st);
     // where the eigen-iteration can sum the split-N partial blocks itself, G is never formed
-    const bool fused = gram_partials_consumable(d) && !std::getenv("SOLAR_GRAM_FINALIZE");
+    const bool fused = gram_partials_consumable(d);
     hipError_t e = launch_gram(X, lengths, B, N, d, bf16, c.partials, c.G, !fused, st);
     if (e != hipSuccess) return SOLAR_ERR_HIP;
     if (timed) timer_mark(call, 1, st);
     e = launch_eig(c.G, fused ? c.partials : nullptr, gram_nsplit(B, N), lengths, B, N, d, r, S, V, info,
-                   eig_params_from_env(), st);
+                   eig_params(), st);
     if (e != hipSuccess) return SOLAR_ERR_HIP;
     if (timed) timer_mark(call, 2, st);
     if (P) {
@@ -138,7 +142,52 @@ hipError_t static_scratch_of_current_device(void** out) {
 
 }  // namespace
 
+namespace solar {
+
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes) {
+    static std::mutex mu;
+    static std::map<std::pair<const void*, int>, size_t> granted;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    size_t& have = granted[std::make_pair(kernel, dev)];
+    if (bytes <= have) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) have = bytes;
+    return e;
+}
+
+int debug_eig_max_iter() { return g_debug_eig_max_iter.load(std::memory_order_relaxed); }
+bool debug_force_guarded_pass() { return g_debug_force_guarded.load(std::memory_order_relaxed) != 0; }
+
+}  // namespace solar
+
 extern "C" {
+
+solar_status solar_debug_option(solar_debug_key key, int value) {
+    switch (key) {
+        case SOLAR_DEBUG_EIG_MAX_ITER:
+            if (value < 0) return SOLAR_ERR_INVALID_ARG;
+            g_debug_eig_max_iter.store(value, std::memory_order_relaxed);
+            return SOLAR_OK;
+        case SOLAR_DEBUG_FORCE_GUARDED_PASS:
+            g_debug_force_guarded.store(value != 0, std::memory_order_relaxed);
+            return SOLAR_OK;
+        default:
+            return SOLAR_ERR_INVALID_ARG;
+    }
+}
+
+solar_status solar_info_status(const int32_t* info_host, int B) {
+    if (!info_host || B <= 0) return SOLAR_ERR_INVALID_ARG;
+    solar_status worst = SOLAR_OK;
+    for (int b = 0; b < B; ++b) {
+        if (info_host[b] < 0) return SOLAR_ERR_INVALID_ARG;
+        if (info_host[b] > 0) worst = SOLAR_ERR_NOT_CONVERGED;
+    }
+    return worst;
+}
 
 const char* solar_status_string(solar_status s) {
     switch (s) {
@@ -147,6 +196,7 @@ const char* solar_status_string(solar_status s) {
         case SOLAR_ERR_UNSUPPORTED: return "unsupported shape or type";
         case SOLAR_ERR_WORKSPACE: return "workspace too small or misaligned";
         case SOLAR_ERR_HIP: return "HIP launch error";
+        case SOLAR_ERR_NOT_CONVERGED: return "eigen-iteration reached its cap for at least one user";
         case SOLAR_ERR_SCRATCH_LIMIT: return "sizes need more scratch than the built-in array of the allocation-free call holds";
         default: return "unknown status";
     }
@@ -304,7 +354,7 @@ solar_status solar_svd_attention(const void* Q, const float* S, const float* V, 
     (void)workspace; (void)workspace_bytes;
     if (!Q || !V || !O || B <= 0 || N <= 0 || d <= 0 || r <= 0 || M <= 0) return SOLAR_ERR_INVALID_ARG;
     if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
-    if (r > d) return SOLAR_ERR_INVALID_ARG;
+    if (r > d || r > N) return SOLAR_ERR_INVALID_ARG;
     if (!supported_shape(d, r)) return SOLAR_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
     const bool bf16 = t == SOLAR_BF16;
@@ -312,16 +362,10 @@ solar_status solar_svd_attention(const void* Q, const float* S, const float* V, 
     switch (mode) {
         case SOLAR_ATTN_SEQ_SOFTMAX:
             if (!P) return SOLAR_ERR_INVALID_ARG;
-            // bf16 inputs take a 16-bit matrix-unit path: single fp16 operands by default
-            // (2e-2 contract), bf16 head + tail operands (about 16 mantissa bits in the scores)
-            // when SOLAR_ATTN_SPLIT is set or S is not supplied; float inputs keep float
-            // arithmetic throughout
-            if (bf16 && S && attention_seq_x32_supported(d, r) && !std::getenv("SOLAR_ATTN_F32") &&
-                !std::getenv("SOLAR_ATTN_SPLIT") && !std::getenv("SOLAR_ATTN_X16"))
+            // bf16 inputs with the factors' S at hand and r a multiple of 4 take the fp16
+            // matrix-unit kernel (2e-2 contract); everything else keeps float arithmetic
+            if (bf16 && S && attention_seq_x32_supported(d, r) && rows_fit_32bit(N, 4u * (size_t)r))
                 e = launch_attention_seq_x32(Q, S, V, P, lengths, B, N, d, r, M, scale, O, st);
-            else if (bf16 && attention_seq_bf16_supported(d, r) && !std::getenv("SOLAR_ATTN_F32"))
-                e = launch_attention_seq_bf16(Q, S, V, P, lengths, B, N, d, r, M, scale,
-                                              std::getenv("SOLAR_ATTN_SPLIT") != nullptr, O, st);
             else
                 e = launch_attention_seq(Q, V, P, lengths, B, N, d, r, M, scale, bf16, O, st);
             break;
@@ -344,8 +388,9 @@ solar_status solar_svd_attention_from_x(const void* Q, const void* X, const floa
     (void)workspace; (void)workspace_bytes;
     if (!Q || !X || !S || !V || !O || B <= 0 || N <= 0 || d <= 0 || r <= 0 || M <= 0) return SOLAR_ERR_INVALID_ARG;
     if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
-    if (r > d) return SOLAR_ERR_INVALID_ARG;
+    if (r > d || r > N) return SOLAR_ERR_INVALID_ARG;
     if (t != SOLAR_BF16 || !attention_seq_x32_from_x_supported(d, r)) return SOLAR_ERR_UNSUPPORTED;
+    if (!rows_fit_32bit(N, 2u * (size_t)d)) return SOLAR_ERR_UNSUPPORTED;
     hipError_t e = launch_attention_seq_x32_from_x(Q, S, V, X, lengths, B, N, d, r, M, scale, O, (hipStream_t)stream);
     return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
 }

@@ -345,14 +345,12 @@ static hipError_t launch_seq_q(const void* Q, const float* V, const float* P,
     dim3 grid(ceil_div(M, 4 * QB * 16) * 8 * ceil_div(B, 8)), block(kAttnThreads * NS);
     if (bf16) {
         auto kern = attention_seq_kernel<D, RB, true, QB, NS>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
     } else {
         auto kern = attention_seq_kernel<D, RB, false, QB, NS>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, V, P, lengths, B, N, r, M, scale, O);
     }
@@ -369,11 +367,6 @@ static hipError_t launch_seq_n(const void* Q, const float* V, const float* P,
                                bool bf16, float* O, hipStream_t stream) {
     const long long wgs = (long long)B * ceil_div(M, 64 * QB);
     int ns = wgs >= 1024 ? 1 : (wgs >= 512 ? 2 : 4);
-    static const int forced = [] {
-        const char* e = std::getenv("SOLAR_ATTN_NS");   // tuning aid
-        return e ? std::atoi(e) : 0;
-    }();
-    if (forced == 1 || forced == 2 || forced == 4) ns = forced;
     // two query blocks per wave leave room for two groups only (four would hold 16 waves to 128
     // registers each, which that variant does not fit; nor does it fit 256 at d = 256, r > 48)
     constexpr int kMaxNs = QB == 1 ? 4 : ((D == 256 && RB == 4) ? 1 : 2);
@@ -430,14 +423,12 @@ hipError_t launch_attention_tokens(const void* Q, const float* S, const float* V
     dim3 grid(ceil_div(M, 64), B), block(256);
     if (bf16) {
         auto kern = attention_tokens_kernel<true>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, d, r, M, scale, softmax ? 1 : 0, O);
     } else {
         auto kern = attention_tokens_kernel<false>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, d, r, M, scale, softmax ? 1 : 0, O);
     }

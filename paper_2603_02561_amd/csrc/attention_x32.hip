@@ -702,14 +702,13 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 template <int D, int RP, bool FUSED>
 hipError_t launch_d(const void* Q, const float* S, const float* V, const void* P, const int32_t* lengths,
                     int B, int N, int r, int M, float scale, float* O, hipStream_t stream) {
-    // debugging aid: skip the optimistic pass
-    const int guarded_only = std::getenv("SOLAR_X32_GUARDED") != nullptr;
+    // debug switch (solar_debug_option): skip the optimistic pass
+    const int guarded_only = debug_force_guarded_pass() ? 1 : 0;
     constexpr int kBuf = kNT * (RP + 8);
     const size_t lds = sizeof(uint16_t) * (3 * (size_t)kBuf + 2 * RP * (size_t)(D + 8) + 2 * D * (size_t)(RP + 8)) + 16;
     dim3 grid(ceil_div(M, kWaves * kQW) * 8 * ceil_div(B, 8)), block(kThreads);
     auto kern = attention_seq_x32_kernel<D, RP, FUSED>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, P, lengths, B, N, r, M, scale, guarded_only, O);
     return hipGetLastError();

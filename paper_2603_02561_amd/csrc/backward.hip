@@ -162,8 +162,7 @@ hipError_t launch_bp(const float* In, const float* W, int B, int rows, float* Ou
     if (gx > maxgx) gx = maxgx;
     if (gx < 1) gx = 1;
     auto kern = backproject_kernel<KR, D>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(gx, B), dim3(kRowWaves * 64), lds, stream, In, W, rows, Out);
     return hipGetLastError();
@@ -193,8 +192,7 @@ hipError_t launch_svd_backward(const float* S, const float* V, const float* P, c
     const size_t extra = sizeof(float) * (size_t)d * (r + 1);
     const int stage_g = base + extra <= 128 * 1024;
     const size_t lds = base + (stage_g ? extra : 0);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(svd_backward_small_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(svd_backward_small_kernel), lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(svd_backward_small_kernel, dim3(B), dim3(kSmallThreads), lds, stream, S, V, S_bar, V_bar,
                        d, r, gap_rel, stage_g, Mt);

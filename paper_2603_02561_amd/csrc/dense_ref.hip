@@ -107,14 +107,12 @@ hipError_t launch_dense_ref(const void* Q, const void* X, const int32_t* lengths
     dim3 grid(ceil_div(M, kDM), B), block(256);
     if (bf16) {
         auto kern = dense_ref_kernel<true>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, X, lengths, N, d, M, scale, O);
     } else {
         auto kern = dense_ref_kernel<false>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, X, lengths, N, d, M, scale, O);
     }

@@ -395,19 +395,12 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     float prev_res = 3.0e38f;
     int it = 0;
     int status = 0;
-    int total_sweeps = 0;
     bool have_ritz = false;
     int cheap_left = prm.mgs_steps;
     int cycle = 0;
-    long long cyc_gemm = 0, cyc_jac = 0, cyc_mgs = 0, cyc_chk = 0;
-    const long long wall0 = wall_clock64();
-    const long long cyc0 = clock64();
     for (;; ++it) {
-        long long t0 = clock64();
         gemm_gq<D, LP, C::GS>(Gop, Qc, Zc);
         __syncthreads();
-        cyc_gemm += clock64() - t0;
-        t0 = clock64();
         // column norms of Z (for the dead-column threshold), Rayleigh quotients and residuals
         if (col < L) {
             const float* q = Qc + col * LD;
@@ -450,14 +443,11 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
             if (it >= prm.max_iter) { status = it; break; }
         }
         __syncthreads();
-        cyc_chk += clock64() - t0;
         if (tid == 0) { sh_bits = 0; sh_bits2 = 0; }
         if (cheap_left > 0) {
             --cheap_left;
             have_ritz = false;
-            t0 = clock64();
             mgs_orthonormalize<D, L>(Zc, Qc, resid, dead2);
-            cyc_mgs += clock64() - t0;
             if (cycle == 0 && cheap_left == 0 && it > 0) {   // the last of the initial cheap steps
                 // Convergence rate seen by this pass: the smallest diagonal entry of the triangular
                 // factor over the r-th largest estimates lambda_(L+1) / lambda_r.  A slowly decaying
@@ -494,14 +484,11 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
         have_ritz = true;
         // orthogonalize the columns of Z (this also rotates them towards Ritz vectors)
         orth_ok = false;
-        t0 = clock64();
         for (int sw = 0; sw < prm.sweeps; ++sw) {
             const float mine = jacobi_sweep<D, L>(Zc, dead2);
-            ++total_sweeps;
             const bool any = __syncthreads_or(mine > prm.tol_orth);
             if (!any) { orth_ok = true; break; }
         }
-        cyc_jac += clock64() - t0;
         // normalize; drop columns that are numerically zero
         if (col < L) {
             const float* z = Zc + col * LD;
@@ -542,18 +529,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
         for (int i = cu; i < D; i += TC) V[((size_t)b * D + i) * r + k] = sgn * q[i];
         if (cu == 0) S[(size_t)b * r + k] = sqrtf(fmaxf(theta[col], 0.f));
     }
-    if (tid == 0 && info) {
-        int v = status;
-        if (prm.debug_counts == 1) v = it * 1000 + total_sweeps;
-        if (prm.debug_counts == 2) v = (int)(cyc_jac / (total_sweeps * (L - 1)));   // cycles per round
-        if (prm.debug_counts == 3) v = (int)(cyc_gemm / (it + 1));                   // cycles per GEMM
-        if (prm.debug_counts == 4) v = (int)(wall_clock64() - wall0);                // 100 MHz ticks
-        if (prm.debug_counts == 5) v = (int)((clock64() - cyc0) / 1000);             // kilo-cycles
-        if (prm.debug_counts == 6) v = (int)cyc_mgs;
-        if (prm.debug_counts == 7) v = (int)cyc_chk;
-        if (prm.debug_counts == 8) v = (int)cyc_jac;
-        info[b] = v;
-    }
+    if (tid == 0 && info) info[b] = status;
 }
 
 // Last step of Algorithm 1 when it is run with passes over H: from W = H^T Y (d x r) and
@@ -687,8 +663,7 @@ hipError_t launch_rsvd_small_t(const float* W, const float* Gy, const int32_t* l
     using C = EigCfg<D, L>;
     const size_t lds = sizeof(float) * ((size_t)C::LP * C::LD + (size_t)L * (L + 1) + 2 * C::LP + 8);
     auto kern = rsvd_small_kernel<D, L>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(B), dim3(kEigThreads), lds, stream, W, Gy, lengths, N, S, V, info, 30);
     return hipGetLastError();
@@ -700,8 +675,7 @@ hipError_t launch_eig_t(const float* G, const float* partials, int nsplit, const
     if (partials && !EigCfg<D, L>::GLDS) return hipErrorInvalidValue;
     const size_t lds = sizeof(float) * EigCfg<D, L>::lds_floats;
     auto kern = eig_topr_kernel<D, L>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(B), dim3(kEigThreads), lds, stream, G, partials, nsplit, lengths, N, r, S, V,
                        info, prm);
@@ -741,7 +715,6 @@ EigParams eig_default_params() {
     p.max_iter = 40;
     p.sweeps = 12;
     p.mgs_steps = 2;
-    p.debug_counts = 0;
     return p;
 }
 

@@ -52,8 +52,7 @@ constexpr size_t gram_reduce_lds() { return sizeof(v4f) * kGramWaves * NP * 64; 
 
 template <typename K>
 static hipError_t gram_allow_lds(K kern, size_t bytes) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)bytes);
+    return allow_dynamic_lds(reinterpret_cast<const void*>(kern), bytes);
 }
 
 #ifndef SOLAR_GRAM_RING
@@ -599,12 +598,8 @@ __global__ __launch_bounds__(256) void gram256_finalize_kernel(const float* __re
 int gram_nsplit(int B, int N) {
     // One workgroup per compute unit (its accumulators leave room for one wave per SIMD, so a
     // second round of workgroups would only queue behind the first), at least 512 rows per
-    // chunk.  SOLAR_GRAM_WGS overrides the target count for tuning.
-    static const int target = [] {
-        const char* e = std::getenv("SOLAR_GRAM_WGS");
-        const int v = e ? std::atoi(e) : 0;
-        return v > 0 ? v : 256;
-    }();
+    // chunk.
+    constexpr int target = 256;
     int want = ceil_div(target, B);
     int cap = ceil_div(N, 512);
     int n = want < cap ? want : cap;
@@ -653,8 +648,7 @@ hipError_t launch_gram(const void* X, const int32_t* lengths, int B, int N, int 
         case 256: {
             const int nsplit = gram_nsplit(B, N);
             dim3 block(kGramWaves * 64), g2(256 * 256 / 256, B);
-            static const bool separate_jobs = std::getenv("SOLAR_GRAM256_JOBS") != nullptr;   // tuning aid
-            if (bf16 && !separate_jobs) {
+            if (bf16) {
                 hipLaunchKernelGGL(gram256_shared_kernel, dim3(nsplit, B), block, 0, stream, X, lengths, N, nsplit,
                                    partials);
                 hipLaunchKernelGGL(gram256_gather_kernel, dim3(10, B), dim3(256), 0, stream, partials, nsplit, G);

@@ -7,6 +7,13 @@
 
 namespace solar {
 
+// api.hip: raises a kernel's limit of dynamic LDS to `bytes`.  The limit is sticky per device
+// and kernel, so the runtime is asked only when a launch needs more than was granted before.
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes);
+// api.hip: the debug switches of solar_debug_option (0 = off)
+int debug_eig_max_iter();
+bool debug_force_guarded_pass();
+
 // gram.hip
 int gram_nsplit(int B, int N);
 size_t gram_partial_floats(int B, int N, int d);
@@ -23,7 +30,6 @@ struct EigParams {
     int max_iter;       // cap on power steps
     int sweeps;         // cap on Jacobi sweeps per power step
     int mgs_steps;      // leading power steps that use a Gram-Schmidt pass instead of Jacobi
-    int debug_counts;   // nonzero: info[] returns 1000*power_steps + sweeps instead of status
 };
 EigParams eig_default_params();
 int eig_block_columns(int d, int r);
@@ -54,12 +60,6 @@ hipError_t launch_attention_seq(const void* Q, const float* V, const float* P,
 hipError_t launch_attention_tokens(const void* Q, const float* S, const float* V, int B, int d,
                                    int r, int M, float scale, bool softmax, bool bf16, float* O,
                                    hipStream_t stream);
-
-// attention_bf16.hip
-bool attention_seq_bf16_supported(int d, int r);
-hipError_t launch_attention_seq_bf16(const void* Q, const float* S, const float* V, const float* P,
-                                     const int32_t* lengths, int B, int N, int d, int r, int M,
-                                     float scale, bool split, float* O, hipStream_t stream);
 
 // attention_x32.hip
 bool attention_seq_x32_supported(int d, int r);

@@ -92,8 +92,7 @@ hipError_t launch_d(const void* In, const float* W, size_t w_stride, int B, int 
 #define SOLAR_ROWGEMM(IB, OB)                                                                        \
     do {                                                                                             \
         auto kern = rowgemm_kernel<D, IB, OB>;                                                       \
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);    \
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);    \
         if (e != hipSuccess) return e;                                                               \
         hipLaunchKernelGGL(kern, grid, block, lds, stream, In, W, w_stride, rows, scale, Out);       \
     } while (0)

@@ -214,11 +214,6 @@ static hipError_t launch_project_d(const void* X, const int32_t* lengths, const 
     const long long want = bf16 ? 256 : 1024;
     int tiles = kProjTilesPerWave;
     while (tiles > 1 && (long long)B * ceil_div(N, 64 * tiles) < want) tiles /= 2;
-    static const int forced = [] {
-        const char* e = std::getenv("SOLAR_PROJECT_TILES");   // tuning aid
-        return e ? std::atoi(e) : 0;
-    }();
-    if (forced >= 1 && forced <= 8) tiles = forced;
     dim3 grid(ceil_div(N, 16 * 4 * tiles), B), block(kProjThreads);
     if (bf16) {
         const uint16_t* Xh = reinterpret_cast<const uint16_t*>(X);
@@ -234,16 +229,14 @@ static hipError_t launch_project_d(const void* X, const int32_t* lengths, const 
                 [[fallthrough]];
             default: {
                 auto kern = project_kernel<D, true>;
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
                 if (e != hipSuccess) return e;
                 hipLaunchKernelGGL(kern, grid, block, lds, stream, X, lengths, V, N, r, RP, tiles, P);
             }
         }
     } else {
         auto kern = project_kernel<D, false>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, X, lengths, V, N, r, RP, tiles, P);
     }

@@ -40,8 +40,9 @@ def test_library_exports_every_declared_symbol(lib):
 def test_status_strings_and_workspace_size(lib):
     lib.solar_status_string.restype = ctypes.c_char_p
     lib.solar_status_string.argtypes = [ctypes.c_int]
-    seen = {lib.solar_status_string(i).decode() for i in range(5)}
-    assert len(seen) == 5 and "ok" in seen
+    seen = {lib.solar_status_string(i).decode() for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen and "unknown status" not in seen
+    assert lib.solar_status_string(99).decode() == "unknown status"
     lib.solar_workspace_bytes.restype = ctypes.c_size_t
     lib.solar_workspace_bytes.argtypes = [ctypes.c_int] * 6
     small = lib.solar_workspace_bytes(1, 1024, 64, 8, 64, 0)
@@ -89,3 +90,25 @@ def test_argument_validation_happens_before_any_launch(lib):
     lib.solar_gram.restype = ci
     assert lib.solar_gram(fake, None, 1, 64, 64, 0, None, fake, 1 << 30, None) == INVALID
     assert lib.solar_gram(fake, None, 1, 64, 48, 0, fake, fake, 1 << 30, None) == UNSUPPORTED
+
+
+def test_info_status_and_debug_options(lib):
+    """Host-side helpers: the verdict over a per-user info array (host memory) and the debug
+    switches, which only store a value."""
+    lib.solar_info_status.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    lib.solar_info_status.restype = ctypes.c_int
+    OK, INVALID, NOT_CONVERGED = 0, 1, 5
+
+    def verdict(values):
+        arr = (ctypes.c_int32 * len(values))(*values)
+        return lib.solar_info_status(arr, len(values))
+    assert verdict([0, 0, 0]) == OK
+    assert verdict([0, 7, 0]) == NOT_CONVERGED
+    assert verdict([0, 7, -1]) == INVALID
+    assert lib.solar_info_status(None, 3) == INVALID
+    lib.solar_debug_option.argtypes = [ctypes.c_int, ctypes.c_int]
+    lib.solar_debug_option.restype = ctypes.c_int
+    assert lib.solar_debug_option(0, 3) == OK and lib.solar_debug_option(0, 0) == OK
+    assert lib.solar_debug_option(0, -1) == INVALID
+    assert lib.solar_debug_option(1, 1) == OK and lib.solar_debug_option(1, 0) == OK
+    assert lib.solar_debug_option(9, 1) == INVALID

@@ -272,6 +272,7 @@ def test_edge_shapes(lib, oracle, name, B, N, d, r, M, dtype, lengths):
     db.factorize()
     torch.cuda.synchronize()
     assert np.all(db.info.cpu().numpy() == 0)
+    assert lib.solar_info_status(db.info) == lib.SOLAR_OK
     f = oracle.svd_factorize(w.X, w.r, w.lengths)
     tol = TOL[dtype]
     for scale in (1.0, 4.0):
@@ -297,16 +298,17 @@ def test_iteration_cap_is_reported_per_user(lib):
     import torch
     w = synth.make_workload("t", 3, 600, 128, 32, 16, synth.BF16, "spectrum", 0.5, 0.05, seed=777)
     db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, True)
-    os.environ["SOLAR_EIG_MAXIT"] = "1"
+    assert lib.solar_debug_option(lib.SOLAR_DEBUG_EIG_MAX_ITER, 1) == lib.SOLAR_OK
     try:
         print("[case] iteration cap 1", flush=True)
         db.factorize()
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("SOLAR_EIG_MAXIT", None)
+        lib.solar_debug_option(lib.SOLAR_DEBUG_EIG_MAX_ITER, 0)
     info = db.info.cpu().numpy()
     print(f"  info {info.tolist()}", flush=True)
     assert np.all(info > 0)
+    assert lib.solar_info_status(db.info) == lib.SOLAR_ERR_NOT_CONVERGED
     assert bool(torch.isfinite(db.S).all()) and bool(torch.isfinite(db.V).all())
     db.factorize()
     torch.cuda.synchronize()

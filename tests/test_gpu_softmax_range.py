@@ -84,13 +84,12 @@ def test_guarded_pass_alone(lib, oracle, r):
     for scale in (1.0, w.sharp_scale):
         want = oracle.svd_attention(w.Q, w.X, f["S"], f["V"], scale, 0, w.lengths)
         for guarded in (False, True):
-            if guarded:
-                os.environ["SOLAR_X32_GUARDED"] = "1"
+            lib.solar_debug_option(lib.SOLAR_DEBUG_FORCE_GUARDED_PASS, 1 if guarded else 0)
             try:
                 db.attention(scale, 0)
                 torch.cuda.synchronize()
             finally:
-                os.environ.pop("SOLAR_X32_GUARDED", None)
+                lib.solar_debug_option(lib.SOLAR_DEBUG_FORCE_GUARDED_PASS, 0)
             got = db.O.cpu().numpy().astype(np.float64)
             err = rel_err(got, want)
             print(f"  scale={scale:.3g} guarded={guarded} err {err:.3e}", flush=True)

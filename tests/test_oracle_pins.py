@@ -451,3 +451,41 @@ def test_svd_backward_truncated_with_vbar_in_span_and_singular_value_part():
     Xp = np.concatenate([X, 5.0 * np.ones((3, d))])[None]
     gm = oracle.svd_backward(Xp, r, S_bar[None], V_bar[None], lengths=np.array([n], dtype=np.int32))[0]
     assert np.all(gm[n:] == 0) and np.allclose(gm[:n], got, atol=1e-12)
+
+
+def test_svd_backward_guard_drops_exactly_the_close_pair():
+    """gap_rel > 0 (the paper states no guard for close singular values; the entry point sets
+    F_ij = 0 for |s_i^2 - s_j^2| <= gap_rel s_1^2).  The gradient is linear in V_bar, and the pair
+    (i, j) enters only through the coefficients A_ij, A_ji of V_bar in the basis V.  So the guarded
+    gradient for a generic V_bar must equal the *unguarded* gradient for V_bar with those two
+    coefficients removed -- and that one is pinned by central finite differences (r = d, so the
+    formula is the whole gradient).  A guard that dropped another pair, or scaled instead of
+    dropping, fails; so does a guard that never fires."""
+    g = rng(43)
+    n, d = 9, 4
+    sig = np.array([3.0, 2.0, 1.98, 0.5])           # s_2^2 - s_3^2 = 0.0796
+    U0, _ = np.linalg.qr(g.standard_normal((n, d)))
+    V0, _ = np.linalg.qr(g.standard_normal((d, d)))
+    X = (U0 * sig) @ V0.T
+    f = oracle.svd_factorize(X[None], d)
+    V = f["V"][0]
+    assert np.allclose(f["S"][0], sig, atol=1e-12)
+    S_bar, V_bar = g.standard_normal(d), g.standard_normal((d, d))
+    gap_rel = 0.02                                   # 0.02 * 9 = 0.18: only the pair (1, 2) is inside
+    s2 = sig * sig
+    close = [(i, j) for i in range(d) for j in range(d) if i != j and abs(s2[i] - s2[j]) <= gap_rel * s2[0]]
+    assert sorted(close) == [(1, 2), (2, 1)]
+    A = V.T @ V_bar
+    A_cut = A.copy()
+    A_cut[1, 2] = 0.0
+    A_cut[2, 1] = 0.0
+    V_bar_cut = V @ A_cut                            # r = d: V is square, V_bar = V A exactly
+    guarded = oracle.svd_backward(X[None], d, S_bar[None], V_bar[None], gap_rel=gap_rel)[0]
+    want = _fd_grad(X, d, S_bar, V_bar_cut)
+    assert np.abs(guarded - want).max() < 1e-5 * max(1.0, np.abs(want).max())
+    # the guard matters here: without it the close pair contributes 1 / 0.0796 times its coefficients
+    unguarded = oracle.svd_backward(X[None], d, S_bar[None], V_bar[None], gap_rel=0.0)[0]
+    assert np.abs(unguarded - guarded).max() > 1.0
+    # and a V_bar without those coefficients does not feel the guard
+    same = oracle.svd_backward(X[None], d, S_bar[None], V_bar_cut[None], gap_rel=gap_rel)[0]
+    assert np.abs(same - guarded).max() < 1e-12 * max(1.0, np.abs(guarded).max())
