@@ -364,7 +364,7 @@ def main() -> int:
         omega = torch.from_numpy(synth.make_omega(w.B, w.d, w.r)).cuda()
         lens_sum = float(np.sum(lens))
         alg1 = {}
-        for q in (0, 1):
+        for q in (0, 1, 2):
             db.factorize_rsvd(omega, q)
             torch.cuda.synchronize()
             ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -256,17 +256,21 @@ solar_status solar_gram(const void* X, const int32_t* lengths, int B, int N, int
                         void* stream);
 
 /*
- * The factorization by Algorithm 1 ("Randomized SVD with Power Iteration") run as printed,
- * with passes over X instead of the Gram matrix: Y = X Omega; n_iter times
- * Omega <- X^T Y, Y = X Omega (no re-orthonormalisation between power steps); Q R = Y;
- * s and R = singular values and right singular vectors of Q^T X.  The QR step is carried
- * by the Cholesky factor of Y^T Y (Q is never formed: Q^T X = R^-T (X^T Y)^T), the small
- * SVD by a one-sided Jacobi.  X is read 2*n_iter + 2 times (plus once for P).
+ * The factorization by Algorithm 1 ("Randomized SVD with Power Iteration") with the passes
+ * over X that it prints, instead of the Gram matrix: Y = X Omega; n_iter times
+ * Omega <- X^T Y, Y = X Omega; Q R = Y; s and R = singular values and right singular vectors
+ * of Q^T X.  One step is added to the printed ones: after every power step Omega is replaced
+ * by an orthonormal basis of its range.  Every output of the algorithm depends on Omega only
+ * through that range, so the result is the printed algorithm's; in float arithmetic the
+ * printed form loses the trailing directions (cond(X Omega) grows by (s_1/s_r)^2 per power
+ * step), this one does not.  The QR step is carried by the Cholesky factor of Y^T Y (Q is
+ * never formed: Q^T X = R^-T (X^T Y)^T), the small SVD by a one-sided Jacobi.  X is read
+ * 2*n_iter + 2 times (plus once for P).
  *   Omega    in  [B,d,r] float   the Gaussian start blocks (the caller draws them)
  *   n_iter   power iterations, >= 0
  *   S, V, P, info   as for solar_svd_factorize; info[b] = -2 when Y^T Y is not numerically
- *            positive definite (the columns of Y have collapsed onto the leading singular
- *            vectors, which the printed algorithm runs into after a few power steps in float)
+ *            positive definite (X Omega has fewer than r independent columns: rank(X) < r, or
+ *            a degenerate Omega)
  * Supported: d in {64, 128}, r in {16, 32, 48, 64}, r <= d.  Workspace:
  * solar_rsvd_workspace_bytes(B, N, d, r) bytes, 256-byte aligned.
  */

@@ -294,6 +294,9 @@ solar_status solar_svd_factorize_rsvd(const void* X, const int32_t* lengths, int
         e = launch_xty(X, Y, lengths, B, N, d, r, bf16, partials, Wb, Gy, st);
         if (e != hipSuccess) return SOLAR_ERR_HIP;
         if (it == n_iter) break;
+        // Omega <- H^T (H Omega), replaced by an orthonormal basis of the same range
+        e = launch_orthonormalize_block(Wb, B, d, r, st);
+        if (e != hipSuccess) return SOLAR_ERR_HIP;
         e = launch_project(X, lengths, Wb, nullptr, B, N, d, r, bf16, Y, st);
         if (e != hipSuccess) return SOLAR_ERR_HIP;
     }

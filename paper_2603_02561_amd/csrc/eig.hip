@@ -538,8 +538,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
 // vectors of Q^T H are the column norms and normalized columns of (Q^T H)^T = W R^-1 once a
 // one-sided Jacobi has made those columns mutually orthogonal.  One workgroup per user, all of
 // it in LDS.  info: 0 ok, > 0 Jacobi sweeps exhausted, -1 bad length, -2 Gy is not numerically
-// positive definite (the columns of Y have collapsed, as they do after too many power steps
-// without re-orthonormalisation).
+// positive definite (Y has fewer than r independent columns).
 template <int D, int L>
 __global__ __launch_bounds__(kEigThreads) void rsvd_small_kernel(
     const float* __restrict__ W, const float* __restrict__ Gy, const int32_t* __restrict__ lengths, int N,
@@ -657,6 +656,60 @@ __global__ __launch_bounds__(kEigThreads) void rsvd_small_kernel(
     if (tid == 0 && info) info[b] = status;
 }
 
+// Re-orthonormalisation of the power-iteration block between two passes over H when Algorithm 1
+// is run as printed: W (d x r, row-major) is replaced by an orthonormal basis of its range.
+// The printed algorithm has no such step; it changes nothing in exact arithmetic (every later
+// quantity depends on the block only through its range), and in float it is what keeps the
+// r columns from collapsing onto the leading singular vector: without it cond(H Omega) grows by
+// (s_1/s_r)^2 per power step.  Two passes of the panelled Gram-Schmidt above ("twice is enough"
+// up to cond(W) of about 1e7); columns that vanish are dropped as zeros.
+template <int D, int L>
+__global__ __launch_bounds__(kEigThreads) void orthonormalize_block_kernel(float* __restrict__ W) {
+    using C = EigCfg<D, L>;
+    constexpr int LP = C::LP, LD = C::LD, TC = C::TC;
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float* Zc = smem;               // [LP][LD]
+    float* Qc = Zc + LP * LD;       // [LP][LD]
+    float* piv = Qc + LP * LD;      // [LP]
+    __shared__ int sh_bits;
+    const int tid = threadIdx.x, b = blockIdx.x;
+    float* Wb = W + (size_t)b * D * L;
+    if (tid == 0) sh_bits = 0;
+    for (int e = tid; e < D * L; e += kEigThreads) Zc[(e % L) * LD + e / L] = Wb[e];
+    __syncthreads();
+    const int col = tid / TC, cu = tid % TC;
+    for (int pass = 0; pass < 2; ++pass) {
+        if (col < L) {
+            const float* z = Zc + col * LD;
+            float nn = 0.f;
+            for (int i = cu; i < D; i += TC) nn += z[i] * z[i];
+            nn = team_sum<TC>(nn);
+            if (cu == 0) atomicMax(&sh_bits, __float_as_int(nn));
+        }
+        __syncthreads();
+        const float dead2 = kDeadRel * kDeadRel * __int_as_float(sh_bits);
+        __syncthreads();
+        if (tid == 0) sh_bits = 0;
+        mgs_orthonormalize<D, L>(Zc, Qc, piv, dead2);
+        if (pass == 0) {
+            for (int e = tid; e < L * LD; e += kEigThreads) Zc[e] = Qc[e];
+            __syncthreads();
+        }
+    }
+    for (int e = tid; e < D * L; e += kEigThreads) Wb[e] = Qc[(e % L) * LD + e / L];
+}
+
+template <int D, int L>
+hipError_t launch_orthonormalize_t(float* W, int B, hipStream_t stream) {
+    using C = EigCfg<D, L>;
+    const size_t lds = sizeof(float) * ((size_t)2 * C::LP * C::LD + C::LP);
+    auto kern = orthonormalize_block_kernel<D, L>;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(B), dim3(kEigThreads), lds, stream, W);
+    return hipGetLastError();
+}
+
 template <int D, int L>
 hipError_t launch_rsvd_small_t(const float* W, const float* Gy, const int32_t* lengths, int B, int N,
                                float* S, float* V, int32_t* info, hipStream_t stream) {
@@ -740,6 +793,15 @@ hipError_t launch_eig(const float* G, const float* partials, int nsplit, const i
         case 256: return launch_eig_d<256>(G, partials, nsplit, lengths, B, N, r, S, V, info, prm, stream);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_orthonormalize_block(float* W, int B, int d, int r, hipStream_t stream) {
+#define SOLAR_ORTH_CASE(DD, LL) \
+    if (d == DD && r == LL) return launch_orthonormalize_t<DD, LL>(W, B, stream);
+    SOLAR_ORTH_CASE(64, 16) SOLAR_ORTH_CASE(64, 32) SOLAR_ORTH_CASE(64, 48) SOLAR_ORTH_CASE(64, 64)
+    SOLAR_ORTH_CASE(128, 16) SOLAR_ORTH_CASE(128, 32) SOLAR_ORTH_CASE(128, 48) SOLAR_ORTH_CASE(128, 64)
+#undef SOLAR_ORTH_CASE
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_rsvd_small(const float* W, const float* Gy, const int32_t* lengths, int B, int N, int d,

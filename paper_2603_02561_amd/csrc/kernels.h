@@ -39,6 +39,8 @@ size_t eig_lds_bytes(int d, int r);
 hipError_t launch_eig(const float* G, const float* partials, int nsplit, const int32_t* lengths, int B, int N,
                       int d, int r, float* S, float* V, int32_t* info, const EigParams& prm, hipStream_t stream);
 
+// W [B][d][r] <- an orthonormal basis of the range of each user's block (rsvd shapes only)
+hipError_t launch_orthonormalize_block(float* W, int B, int d, int r, hipStream_t stream);
 hipError_t launch_rsvd_small(const float* W, const float* Gy, const int32_t* lengths, int B, int N, int d,
                              int r, float* S, float* V, int32_t* info, hipStream_t stream);
 

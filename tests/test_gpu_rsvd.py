@@ -1,15 +1,18 @@
-"""GPU parity of the factorization by Algorithm 1 run as printed (passes over X, QR through
-the Cholesky factor of Y^T Y, small SVD by one-sided Jacobi) against the double-precision
-oracle of the same algorithm on the same Gaussian start blocks.
+"""GPU parity of the factorization by Algorithm 1 (passes over X, QR through the Cholesky factor
+of Y^T Y, small SVD by one-sided Jacobi) against the double-precision oracle of the printed
+algorithm on the same Gaussian start blocks.
 
-Tolerances.  With no power step the two sides differ by float rounding of well-conditioned
-steps: singular values to 1e-3 of the largest (the bf16 inputs' exact-rank case loses the
-most: its smallest singular values sit 1e-3 below the largest), projectors V V^T to 1e-4.
-Every power step multiplies the condition number of Y = H Omega by (sigma_1/sigma_r)^2 and the
-Cholesky factor of Y^T Y squares it again, so in float the printed algorithm either loses
-digits or reports info = -2 (a Cholesky pivot of Y^T Y below 1e-5 of its diagonal entry) and
-returns zeros.  Both outcomes are accepted for n_iter >= 1; what is not flagged must be within
-2e-2 / 1e-3 after one power step and within 1e-1 / 1e-2 after two.
+The oracle runs the power steps exactly as printed, with no re-orthonormalisation, which double
+precision can afford.  The library replaces the block by an orthonormal basis of its range after
+every power step: every output of the algorithm depends on the block only through its range, so
+the two compute the same thing, and the library's float arithmetic survives the power steps
+(without that step cond(H Omega) grows by (sigma_1/sigma_r)^2 per power step and the float
+Cholesky factor of Y^T Y breaks down after the first one on the headline workload).
+
+Tolerances.  No power step: singular values to 1e-3 of the largest (the bf16 inputs' exact-rank
+case loses the most: its smallest singular values sit 1e-3 below the largest and Y = H Omega
+inherits the conditioning of the raw Gaussian block), projectors V V^T to 1e-4.  One or two power
+steps: 1e-5 for both (measured at most 3e-6), and no user may be flagged.
 """
 import numpy as np
 import pytest
@@ -68,14 +71,9 @@ def test_rsvd_factorize(lib, oracle, name, w):
         P = db.P.cpu().numpy().astype(np.float64)
         info = db.info.cpu().numpy()
         f = oracle.rsvd_alg1(w.X, Om, q, w.lengths)
-        tol_s, tol_p = [(1e-3, 1e-4), (2e-2, 1e-3), (1e-1, 1e-2)][q]
+        tol_s, tol_p = [(1e-3, 1e-4), (1e-5, 1e-5), (1e-5, 1e-5)][q]
         for b in range(w.B):
-            if info[b] == -2:
-                assert q >= 1, "no breakdown is acceptable without power steps"
-                assert np.all(S[b] == 0) and np.all(V[b] == 0)
-                print(f"  user {b}: Y^T Y not positive definite in float (flagged)", flush=True)
-                continue
-            assert info[b] == 0
+            assert info[b] == 0, f"user {b} flagged {info[b]} with {q} power steps"
             s_err = np.abs(S[b] - f["S"][b]).max() / f["S"][b][0]
             proj_err = np.abs(V[b] @ V[b].T - f["V"][b] @ f["V"][b].T).max()
             orth = np.abs(V[b].T @ V[b] - np.eye(w.r)).max()
@@ -88,15 +86,49 @@ def test_rsvd_factorize(lib, oracle, name, w):
             assert np.all(np.diff(S[b]) <= 0)
 
 
+def test_rsvd_headline_size_with_power_steps(lib, oracle):
+    """The headline workload (B=64, N=10000, d=128, r=32, bf16, spectrum 1/k + noise), where
+    sigma_1/sigma_32 = 32: no user may be flagged after one or two power steps, V^T V = I for
+    every user (P^T P = diag(S^2) is not a property of the randomized algorithm: its V are the
+    singular vectors of Q^T H, not of H), and four users agree with the oracle of the printed
+    algorithm."""
+    import torch
+    w = synth.make_config("C3")
+    db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, True)
+    Om = synth.make_omega(w.B, w.d, w.r)
+    Omd = torch.from_numpy(Om).cuda()
+    users = [0, 21, 42, 63]
+    for q in (1, 2):
+        print(f"[case] rsvd C3 n_iter={q}", flush=True)
+        db.factorize_rsvd(Omd, q)
+        torch.cuda.synchronize()
+        info = db.info.cpu().numpy()
+        assert np.all(info == 0), info
+        V = db.V.double()
+        eye = torch.eye(w.r, dtype=torch.float64, device=V.device)
+        vtv = (V.transpose(1, 2) @ V - eye).abs().amax().item()
+        print(f"  all users: |VtV-I| {vtv:.2e}", flush=True)
+        assert vtv < 2e-5
+        f = oracle.rsvd_alg1(w.X[users], Om[users], q, w.lengths[users])
+        Sg = db.S.cpu().numpy().astype(np.float64)
+        Vg = db.V.cpu().numpy().astype(np.float64)
+        for i, u in enumerate(users):
+            s_err = np.abs(Sg[u] - f["S"][i]).max() / f["S"][i][0]
+            proj_err = np.abs(Vg[u] @ Vg[u].T - f["V"][i] @ f["V"][i].T).max()
+            print(f"  user {u}: S {s_err:.2e} proj {proj_err:.2e}", flush=True)
+            assert s_err < 1e-5 and proj_err < 1e-4
+
+
+@pytest.mark.parametrize("n_iter", [0, 1])
 @pytest.mark.parametrize("name,w", WORKLOADS[:2], ids=IDS[:2])
-def test_rsvd_then_attention(lib, oracle, name, w):
-    """mode 0 on the factors of Algorithm 1 (no power step) against the oracle's attention on the
-    oracle's factors of the same algorithm."""
+def test_rsvd_then_attention(lib, oracle, name, w, n_iter):
+    """mode 0 on the factors of Algorithm 1 against the oracle's attention on the oracle's
+    factors of the same algorithm."""
     import torch
     db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, w.dtype == synth.BF16)
     Om = synth.make_omega(w.B, w.d, w.r)
-    db.factorize_rsvd(torch.from_numpy(Om).cuda(), 0)
-    f = oracle.rsvd_alg1(w.X, Om, 0, w.lengths)
+    db.factorize_rsvd(torch.from_numpy(Om).cuda(), n_iter)
+    f = oracle.rsvd_alg1(w.X, Om, n_iter, w.lengths)
     for scale in (1.0, w.sharp_scale):
         db.attention(scale, 0)
         torch.cuda.synchronize()
