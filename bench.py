@@ -197,18 +197,21 @@ def main() -> int:
     # the pipelined pass below gives the throughput.
     ser_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
               for _ in range(args.steps)]
+    ser_step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     ser_start = torch.cuda.Event(enable_timing=True)
     ser_stop = torch.cuda.Event(enable_timing=True)
     binding.solar_phase_timing_begin()
     torch.cuda.synchronize()
     with torch.cuda.stream(streams[0]):
         ser_start.record()
+        ser_step_ev[0].record()
         for i in range(args.steps):
             db = sets[i % n_sets]
             factorize(db)
             ser_ev[i][0].record()
             attend(db)
             ser_ev[i][1].record()
+            ser_step_ev[i + 1].record()
         ser_stop.record()
     torch.cuda.synchronize()
     ser_calls, ser_phase = binding.solar_phase_timing_end()
@@ -216,6 +219,14 @@ def main() -> int:
             "project": ser_phase[2] / max(ser_calls, 1),
             "attention": sum(a.elapsed_time(b) for a, b in ser_ev) / args.steps,
             "step": ser_start.elapsed_time(ser_stop) / args.steps}
+    step_times = sorted(ser_step_ev[i].elapsed_time(ser_step_ev[i + 1]) for i in range(args.steps))
+    attn_times = sorted(a.elapsed_time(b) for a, b in ser_ev)
+
+    def pct(v, q):
+        return v[min(len(v) - 1, int(q * len(v)))]
+    solo_spread = {"step_ms": {"p10": pct(step_times, 0.1), "median": pct(step_times, 0.5), "p90": pct(step_times, 0.9)},
+                   "attention_ms": {"p10": pct(attn_times, 0.1), "median": pct(attn_times, 0.5),
+                                    "p90": pct(attn_times, 0.9)}}
 
     attn_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                for _ in range(args.steps)]
@@ -285,8 +296,9 @@ def main() -> int:
     work = {
         # read X once, write G
         "gram": ("hbm", float(np.sum(lens) * w.d * e + w.B * w.d * w.d * 4)),
-        # read X once, write P
-        "project": ("hbm", float(np.sum(lens) * w.d * e + np.sum(lens) * w.r * 4)),
+        # read the valid rows of X once, write P: all N rows of it, because the rows past the valid
+        # length are part of the output (zeros)
+        "project": ("hbm", float(np.sum(lens) * w.d * e + w.B * w.N * w.r * 4)),
         # Qt = Q V, S = Qt P^T, Z = W P, O = Z V^T
         "attention": ("mfma", float(np.sum(4.0 * w.M * lens * w.r) + w.B * 4.0 * w.M * w.r * w.d)),
     }
@@ -326,6 +338,9 @@ def main() -> int:
             "achieved": kernels[dominant]["alone"]["achieved"], "peak": kernels[dominant]["peak"],
             "unit": kernels[dominant]["unit"], "frac": kernels[dominant]["alone"]["frac"],
             "traffic": traffic,
+            "traffic_source": None if traffic is None else
+            "HBM fetch + write bytes of one launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs "
+            "summarised in profiles/hbm_traffic_C3.txt (a constant of this script, not measured in this run)",
             "achieved_pipelined": kernels[dominant]["pipelined"]["achieved"],
             "frac_pipelined": kernels[dominant]["pipelined"]["frac"],
             "note": f"achieved = algorithmic work of one launch / its average HIP-event duration over "
@@ -341,7 +356,9 @@ def main() -> int:
         "unit": "user-sequences/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 inputs, f32 accumulate" if bf16 else "f32",
+        "vs_baseline": None,
+        "dtype": ("bf16 inputs; fp16 MFMA operands for P, Q V and the softmax weights in the attention kernel, "
+                  "bf16 MFMA operands elsewhere; f32 accumulate") if bf16 else "f32",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} N={w.N} d={w.d} r={w.r} M={w.M} "
                                f"{'bf16' if bf16 else 'f32'} inputs, mode 0, scale {scale}",
@@ -349,7 +366,7 @@ def main() -> int:
         "phase_ms": phases, "dominant_kernel": dominant, "kernels": kernels,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
         "fused_projection": fused,
-        "streams": n_streams, "serial_pass_ms": solo,
+        "streams": n_streams, "serial_pass_ms": solo, "serial_pass_spread": solo_spread,
         "value_serial": w.B / (solo["step"] * 1e-3),
         "users_not_converged": info_bad,
         "roofline": roof,

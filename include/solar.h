@@ -282,7 +282,7 @@ solar_status solar_svd_factorize_rsvd(const void* X, const int32_t* lengths, int
 
 /*
  * Per-phase timing of solar_svd_factorize, for benchmarks.  After
- * solar_phase_timing_begin() every factorize call (up to 256 of them) records HIP
+ * solar_phase_timing_begin() every factorize call records HIP
  * events on its stream around its three phases: the Gram contraction, the
  * eigen-iteration and the projection (Algorithm 1's power-iteration product, its
  * basis/small-SVD steps, and P = X V).  solar_phase_timing_end() waits for the

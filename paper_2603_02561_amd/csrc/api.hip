@@ -2,10 +2,12 @@
 // carving and kernel launches on the caller's stream.  See include/solar.h.
 #include "../../include/solar.h"
 
+#include <array>
 #include <atomic>
 #include <map>
 #include <mutex>
 #include <utility>
+#include <vector>
 
 #include "kernels.h"
 
@@ -48,19 +50,18 @@ Carve carve(void* ws, int B, int N, int d) {
 // Optional per-phase timing of solar_svd_factorize: HIP events recorded on the
 // caller's stream at the phase boundaries.  Host-side bookkeeping only.
 struct PhaseTimer {
-    static constexpr int kMaxCalls = 256;
     bool enabled = false;
     int calls = 0;
-    hipEvent_t ev[kMaxCalls][4];
-    int created = 0;
+    std::vector<std::array<hipEvent_t, 4>> ev;   // one set per timed call, created on demand, kept
 };
 PhaseTimer g_timer;
 
 void timer_mark(int call, int slot, hipStream_t st) {
-    if (!g_timer.enabled || call >= PhaseTimer::kMaxCalls) return;
-    while (g_timer.created <= call) {
-        for (int i = 0; i < 4; ++i) (void)hipEventCreate(&g_timer.ev[g_timer.created][i]);
-        ++g_timer.created;
+    if (!g_timer.enabled) return;
+    while ((int)g_timer.ev.size() <= call) {
+        std::array<hipEvent_t, 4> e;
+        for (int i = 0; i < 4; ++i) (void)hipEventCreate(&e[i]);
+        g_timer.ev.push_back(e);
     }
     (void)hipEventRecord(g_timer.ev[call][slot], st);
 }
@@ -112,7 +113,7 @@ solar_status factorize_enqueue(const void* X, const int32_t* lengths, int B, int
     }
     if (timed) {
         timer_mark(call, 3, st);
-        if (g_timer.enabled && call < PhaseTimer::kMaxCalls) g_timer.calls = call + 1;
+        if (g_timer.enabled) g_timer.calls = call + 1;
     }
     return SOLAR_OK;
 }

@@ -119,7 +119,7 @@ template <int D, int RP, bool FUSED>
 __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const void* __restrict__ Qv, const float* __restrict__ S, const float* __restrict__ V,
     const void* __restrict__ Pin, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
-    float scale, int guarded_only, float* __restrict__ O) {
+    float scale, int guarded_only, int longest_first, float* __restrict__ O) {
     static_assert(RP == 32 || RP == 64, "one or two 32-rank halves");
     static_assert(RP == 32 || D <= 128, "the bf16 images of V for 64 ranks of d = 256 do not fit LDS");
     constexpr int LDR = RP + 8, kBuf = kNT * LDR;
@@ -138,10 +138,31 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     // get ids that agree modulo 8, so they share one XCD and its L2 holds that user's P once.
     const int mtiles = ceil_div(M, kWaves * kQW);
     const int slot_id = blockIdx.x >> 3;
-    const int b = (slot_id / mtiles) * 8 + (blockIdx.x & 7);
-    if (b >= B) return;   // uniform over the workgroup
+    const int place = (slot_id / mtiles) * 8 + (blockIdx.x & 7);
+    if (place >= B) return;   // uniform over the workgroup
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n32 = lane & 31, h = lane >> 5;
+    // When the launch has more workgroups than the GPU holds at once, the users are taken in order of
+    // decreasing length (ties by index), so that the long sequences start first and the short
+    // ones fill the tail: the workgroup at place k takes the user of rank k.
+    int b = place;
+    if (longest_first) {   // uniform over the launch
+        int* lens = reinterpret_cast<int*>(tiles);
+        for (int u = tid; u < B; u += kThreads) lens[u] = user_len(lengths, u, N);
+        __syncthreads();
+        for (int u = tid; u < B; u += kThreads) {
+            const int lu = lens[u];
+            int rank = 0;
+            for (int j = 0; j < B; ++j) {
+                const int lj = lens[j];
+                rank += (lj > lu || (lj == lu && j < u)) ? 1 : 0;
+            }
+            if (rank == place) *redo = u;   // exactly one thread of the workgroup
+        }
+        __syncthreads();
+        b = *redo;
+        __syncthreads();
+    }
     const int len = user_len(lengths, b, N);
     const int m_wave = (slot_id % mtiles) * (kWaves * kQW) + wave * kQW;
     // P is scaled into [-1, 1] by the largest singular value before it is rounded to fp16
@@ -707,10 +728,14 @@ hipError_t launch_d(const void* Q, const float* S, const float* V, const void* P
     constexpr int kBuf = kNT * (RP + 8);
     const size_t lds = sizeof(uint16_t) * (3 * (size_t)kBuf + 2 * RP * (size_t)(D + 8) + 2 * D * (size_t)(RP + 8)) + 16;
     dim3 grid(ceil_div(M, kWaves * kQW) * 8 * ceil_div(B, 8)), block(kThreads);
+    // ranking the users costs every workgroup B^2 / 512 comparisons per thread: worth it only when the
+    // launch runs in several rounds of workgroups and the lengths can differ
+    const int longest_first = lengths != nullptr && grid.x > 256 && B <= 512;
     auto kern = attention_seq_x32_kernel<D, RP, FUSED>;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, P, lengths, B, N, r, M, scale, guarded_only, O);
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, P, lengths, B, N, r, M, scale, guarded_only,
+                       longest_first, O);
     return hipGetLastError();
 }
 

@@ -19,6 +19,18 @@ namespace {
 constexpr int kProjThreads = 256;
 constexpr int kProjTilesPerWave = 8;  // 16-row tiles handled by one wave (fewer in small launches)
 
+// The 16 rows from n0 on (as far as they exist) of one user's P set to zero by one wave: the rows
+// are contiguous in memory, so the wave fills them with 16-byte stores when r is a multiple of 4.
+__device__ __forceinline__ void zero_rows(float* Pb, int n0, int N, int r, int lane) {
+    const int rows = min(16, N - n0);
+    float* dst = Pb + (size_t)n0 * r;
+    if ((r & 3) == 0) {
+        for (int e = lane; e < rows * (r >> 2); e += 64) reinterpret_cast<v4f*>(dst)[e] = v4f{0.f, 0.f, 0.f, 0.f};
+    } else {
+        for (int e = lane; e < rows * r; e += 64) dst[e] = 0.f;
+    }
+}
+
 template <int D, bool BF16>
 __global__ __launch_bounds__(kProjThreads) void project_kernel(
     const void* __restrict__ Xv, const int32_t* __restrict__ lengths, const float* __restrict__ V,
@@ -47,10 +59,7 @@ __global__ __launch_bounds__(kProjThreads) void project_kernel(
         const int n = n0 + i16;
         if (n0 >= len) {
             // rows past the valid length: P is defined to be zero there
-            for (int e = lane; e < 16 * r; e += 64) {
-                const int rr = n0 + e / r;
-                if (rr < N) Pb[(size_t)rr * r + e % r] = 0.f;
-            }
+            zero_rows(Pb, n0, N, r, lane);
             continue;
         }
         // one row per lane: D/16 quads of columns
@@ -166,10 +175,7 @@ __global__ __launch_bounds__(kProjThreads) void project_bf16_kernel(
         const int n = n0 + i16;
         if (n0 >= len) {
             // rows past the valid length: P is defined to be zero there
-            for (int e = lane; e < 16 * r; e += 64) {
-                const int rr = n0 + e / r;
-                if (rr < N) Pb[(size_t)rr * r + e % r] = 0.f;
-            }
+            zero_rows(Pb, n0, N, r, lane);
         } else {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
