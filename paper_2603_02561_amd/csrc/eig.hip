@@ -136,60 +136,148 @@ struct EigCfg {
     static constexpr size_t lds_floats = (size_t)2 * LP * LD + 3 * LP + 8 + (GLDS ? (size_t)D * GS : 0);
 };
 
-// One cyclic sweep of one-sided Jacobi over the L columns of Zc: L-1 rounds of L/2
-// disjoint column pairs (round-robin tournament), one team of TJ lanes per pair.  Returns this thread's largest |cos| met in the sweep.
+// One cyclic sweep of one-sided Jacobi over the L columns of Zc; returns this thread's largest
+// |cos| met in the sweep.
+//
+// A rotation needs two columns and a round of disjoint rotations touches every column, so a
+// sweep that keeps the columns in LDS between rounds moves the whole block through LDS and meets
+// a workgroup barrier once per round: 39 times per sweep at 40 columns, about 640 of a round's
+// 1280 cycles.  Here the columns are dealt to the waves in half-groups of G = 64 / T columns (T
+// lanes per column pair) and a wave keeps two half-groups A, B in registers for G rounds:
+// team i of the wave holds A[i] and, in round j, B[(i + j) mod G], which the teams pass on with
+// lane permutations; after G rounds every column of A has met every column of B.  The half-groups
+// meet each other in a round-robin tournament of H - 1 such super-rounds, with LDS and the
+// workgroup barrier only between them, and the pairs inside a half-group are taken first, G - 1
+// rounds through LDS.  The number of rotations per sweep is that of any cyclic ordering; the
+// barriers drop from L - 1 to (H - 1) + (G - 1).
+#ifndef SOLAR_JAC_T
+#define SOLAR_JAC_T 16
+#endif
+// the widest team (at most SOLAR_JAC_T lanes, a float4 per lane at least) whose waves fit the workgroup
+__host__ __device__ constexpr int jacobi_team_lanes(int d, int l) {
+    for (int t = SOLAR_JAC_T; t > 8; t /= 2) {
+        const int g = 64 / t;
+        if (4 * t <= d && (l + 2 * g - 1) / (2 * g) <= kEigWaves) return t;
+    }
+    return 8;
+}
+
+template <int D, int L>
+struct JacobiCfg {
+    static constexpr int T = jacobi_team_lanes(D, L);   // lanes per column pair
+    static constexpr int G = 64 / T;                    // column pairs per wave = columns per half-group
+    static constexpr int NW = (L + 2 * G - 1) / (2 * G);  // waves that hold columns
+    static constexpr int H = 2 * NW;                    // half-groups
+    static constexpr int LPAD = H * G;                  // columns including the (zero) padding
+    static constexpr int CH = D / (4 * T);              // float4 per lane and column
+    static_assert(NW <= kEigWaves, "one wave per pair of half-groups");
+    static_assert(LPAD <= EigCfg<D, L>::LP, "the padding columns exist in LDS");
+    static_assert(LPAD / 2 * T <= kEigThreads, "one team per pair in the rounds through LDS");
+    static_assert(D % (4 * T) == 0 && CH >= 1, "whole float4 per lane");
+};
+
+// the rotation of one column pair held by a team of T lanes as CH float4 per lane and column;
+// columns that have collapsed to rounding noise are left alone (dropped later)
+template <int T, int CH>
+__device__ __forceinline__ void rotate_pair(v4f (&a)[CH], v4f (&c)[CH], float dead2, float& offmax) {
+    float al = 0.f, be = 0.f, ga = 0.f;
+#pragma unroll
+    for (int k = 0; k < CH; ++k) {
+        al += a[k].x * a[k].x + a[k].y * a[k].y + a[k].z * a[k].z + a[k].w * a[k].w;
+        be += c[k].x * c[k].x + c[k].y * c[k].y + c[k].z * c[k].z + c[k].w * c[k].w;
+        ga += a[k].x * c[k].x + a[k].y * c[k].y + a[k].z * c[k].z + a[k].w * c[k].w;
+    }
+    al = team_sum<T>(al);
+    be = team_sum<T>(be);
+    ga = team_sum<T>(ga);
+    if (al > dead2 && be > dead2) {
+        const float cosv = fabsf(ga) * __builtin_amdgcn_rsqf(al) * __builtin_amdgcn_rsqf(be);
+        offmax = fmaxf(offmax, cosv);
+        if (cosv > kSkipCos) {
+            const float zeta = 0.5f * (be - al) * __builtin_amdgcn_rcpf(ga);
+            const float t = copysignf(1.f, zeta) *
+                            __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+            const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
+            const float sn = cs * t;
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                const v4f x = a[k], y = c[k];
+                a[k] = cs * x - sn * y;
+                c[k] = sn * x + cs * y;
+            }
+        }
+    }
+}
+
+// pair number k of round rho of a round-robin tournament of n players (n even): player n - 1
+// stays, the others go round
+__device__ __forceinline__ void tournament_pair(int n, int rho, int k, int& p, int& q) {
+    p = rho + k;
+    q = rho - k;
+    if (p >= n - 1) p -= n - 1;
+    if (q < 0) q += n - 1;
+    if (k == 0) p = n - 1;
+}
+
 template <int D, int L>
 __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
-    using C = EigCfg<D, L>;
-    constexpr int T = C::TJ, CH = C::CH, LD = C::LD, NPAIR = C::NPAIR;
-    const int tid = threadIdx.x;
-    const int team = tid / T, u = tid % T;
+    using J = JacobiCfg<D, L>;
+    constexpr int T = J::T, G = J::G, CH = J::CH, LD = EigCfg<D, L>::LD;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int u = tid % T;
     float offmax = 0.f;
+    v4f a[CH], c[CH];
+    auto load = [&](v4f (&dst)[CH], int col) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < CH; ++k) dst[k] = *reinterpret_cast<const v4f*>(Zc + col * LD + 4 * u + 4 * T * k);
+    };
+    auto store = [&](const v4f (&src)[CH], int col) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < CH; ++k) *reinterpret_cast<v4f*>(Zc + col * LD + 4 * u + 4 * T * k) = src[k];
+    };
+    // the pairs inside every half-group: G - 1 rounds through LDS, one team per pair
+    if constexpr (G > 1) {
+        const int team = tid / T;
+        const int hg = team / (G / 2), k = team % (G / 2);
 #pragma unroll 1
-    for (int rho = 0; rho < L - 1; ++rho) {
-        if (team < NPAIR) {
-            // round-robin tournament: pair 0 is (L-1, rho), pair k is
-            // ((rho+k) mod (L-1), (rho-k) mod (L-1))
-            int p = rho + team, q = rho - team;
-            if (p >= L - 1) p -= L - 1;
-            if (q < 0) q += L - 1;
-            if (team == 0) p = L - 1;
-            float* zp = Zc + p * LD + 4 * u;
-            float* zq = Zc + q * LD + 4 * u;
-            v4f a[CH], c[CH];
-#pragma unroll
-            for (int k = 0; k < CH; ++k) {
-                a[k] = *reinterpret_cast<const v4f*>(zp + 4 * T * k);
-                c[k] = *reinterpret_cast<const v4f*>(zq + 4 * T * k);
+        for (int rho = 0; rho < G - 1; ++rho) {
+            if (team < J::LPAD / 2) {
+                int p, q;
+                tournament_pair(G, rho, k, p, q);
+                load(a, hg * G + p);
+                load(c, hg * G + q);
+                rotate_pair<T, CH>(a, c, dead2, offmax);
+                store(a, hg * G + p);
+                store(c, hg * G + q);
             }
-            float al = 0.f, be = 0.f, ga = 0.f;
+            __syncthreads();
+        }
+    }
+    // the pairs between half-groups: wave w holds the half-groups of pair w of the super-round
+    const int i = lane / T;
+#pragma unroll 1
+    for (int s = 0; s < J::H - 1; ++s) {
+        if (wave < J::NW) {
+            int ha, hb;
+            tournament_pair(J::H, s, wave, ha, hb);
+            load(a, ha * G + i);
+            load(c, hb * G + i);
 #pragma unroll
-            for (int k = 0; k < CH; ++k) {
-                al += a[k].x * a[k].x + a[k].y * a[k].y + a[k].z * a[k].z + a[k].w * a[k].w;
-                be += c[k].x * c[k].x + c[k].y * c[k].y + c[k].z * c[k].z + c[k].w * c[k].w;
-                ga += a[k].x * c[k].x + a[k].y * c[k].y + a[k].z * c[k].z + a[k].w * c[k].w;
-            }
-            al = team_sum<T>(al);
-            be = team_sum<T>(be);
-            ga = team_sum<T>(ga);
-            // columns that have collapsed to rounding noise are left alone (dropped later)
-            if (al > dead2 && be > dead2) {
-                const float cosv = fabsf(ga) * __builtin_amdgcn_rsqf(al) * __builtin_amdgcn_rsqf(be);
-                offmax = fmaxf(offmax, cosv);
-                if (cosv > kSkipCos) {
-                    const float zeta = 0.5f * (be - al) * __builtin_amdgcn_rcpf(ga);
-                    const float t = copysignf(1.f, zeta) *
-                                    __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
-                    const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
-                    const float sn = cs * t;
+            for (int j = 0; j < G; ++j) {
+                rotate_pair<T, CH>(a, c, dead2, offmax);
+                if (j + 1 < G) {
+                    // team i takes over the B column of team i + 1
 #pragma unroll
                     for (int k = 0; k < CH; ++k) {
-                        const v4f x = a[k], y = c[k];
-                        *reinterpret_cast<v4f*>(zp + 4 * T * k) = cs * x - sn * y;
-                        *reinterpret_cast<v4f*>(zq + 4 * T * k) = sn * x + cs * y;
+                        c[k].x = __shfl(c[k].x, (lane + T) & 63);
+                        c[k].y = __shfl(c[k].y, (lane + T) & 63);
+                        c[k].z = __shfl(c[k].z, (lane + T) & 63);
+                        c[k].w = __shfl(c[k].w, (lane + T) & 63);
                     }
                 }
             }
+            store(a, ha * G + i);
+            store(c, hb * G + (i + G - 1) % G);
         }
         __syncthreads();
     }
