@@ -114,6 +114,40 @@ def test_gram_d256_bf16_ragged_lengths(lib, oracle):
     assert torch.equal(G, G2)
 
 
+@pytest.mark.parametrize("d,bf16,B,N", [(128, True, 37, 700), (64, False, 70, 333), (128, False, 5, 3000),
+                                       (128, True, 300, 90)])
+def test_gram_ragged_lengths_many_users(lib, oracle, d, bf16, B, N):
+    """d <= 128 with lengths from a single row to the full length (chunks that end up empty or
+    ragged), more users than compute units and fewer, an unstructured matrix (a misplaced block
+    shows in every entry), the result bitwise repeatable; and the same batch without a lengths
+    array."""
+    import torch
+    rng = np.random.default_rng(9000 + d + B)
+    lengths = rng.integers(1, N + 1, size=B).astype(np.int32)
+    lengths[0], lengths[-1], lengths[B // 2] = 1, N, 33
+    X = rng.standard_normal((B, N, d)).astype(np.float32)
+    Q = rng.standard_normal((B, 2, d)).astype(np.float32)
+    if bf16:
+        X, Q = synth.round_to_bf16(X), synth.round_to_bf16(Q)
+    db = lib.DeviceBatch(X, Q, lengths, 4, bf16)
+    G = torch.empty((B, d, d), dtype=torch.float32, device="cuda")
+    print(f"[case] gram ragged d={d} bf16={bf16} B={B} N={N} lengths {lengths[:6].tolist()}...", flush=True)
+    lib.solar_gram(db.X, db.lengths, G, db.workspace)
+    torch.cuda.synchronize()
+    err = rel_err(G.cpu().numpy(), oracle.gram(X, lengths))
+    print(f"  gram err {err:.3e}", flush=True)
+    assert err < 2e-6
+    G2 = torch.empty_like(G)
+    lib.solar_gram(db.X, db.lengths, G2, db.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(G, G2)
+    # no lengths array: every user has N rows
+    db2 = lib.DeviceBatch(X, Q, None, 4, bf16)
+    lib.solar_gram(db2.X, None, G, db2.workspace)
+    torch.cuda.synchronize()
+    assert rel_err(G.cpu().numpy(), oracle.gram(X, None)) < 2e-6
+
+
 @pytest.mark.parametrize("name,w", WORKLOADS, ids=IDS)
 def test_dense_reference(lib, oracle, name, w):
     import torch
