@@ -219,6 +219,45 @@ __device__ __forceinline__ void tournament_pair(int n, int rho, int k, int& p, i
     if (k == 0) p = n - 1;
 }
 
+// The same rotation when the squared norms of the two columns are known: only the inner product
+// is formed, and the norms follow the rotation in closed form (alpha' = alpha - t gamma,
+// beta' = beta + t gamma for the rotation that makes the pair orthogonal).
+template <int T, int CH>
+__device__ __forceinline__ void rotate_pair_with_norms(v4f (&a)[CH], v4f (&c)[CH], float& al, float& be,
+                                                       float dead2, float& offmax) {
+    float ga = 0.f;
+#pragma unroll
+    for (int k = 0; k < CH; ++k) ga += a[k].x * c[k].x + a[k].y * c[k].y + a[k].z * c[k].z + a[k].w * c[k].w;
+    ga = team_sum<T>(ga);
+    if (al > dead2 && be > dead2) {
+        const float cosv = fabsf(ga) * __builtin_amdgcn_rsqf(al) * __builtin_amdgcn_rsqf(be);
+        offmax = fmaxf(offmax, cosv);
+        if (cosv > kSkipCos) {
+            const float zeta = 0.5f * (be - al) * __builtin_amdgcn_rcpf(ga);
+            const float t = copysignf(1.f, zeta) *
+                            __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+            const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
+            const float sn = cs * t;
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                const v4f x = a[k], y = c[k];
+                a[k] = cs * x - sn * y;
+                c[k] = sn * x + cs * y;
+            }
+            al -= t * ga;
+            be += t * ga;
+        }
+    }
+}
+
+template <int CH>
+__device__ __forceinline__ float norm2_ch(const v4f (&a)[CH]) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < CH; ++k) s += a[k].x * a[k].x + a[k].y * a[k].y + a[k].z * a[k].z + a[k].w * a[k].w;
+    return s;
+}
+
 template <int D, int L>
 __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
     using J = JacobiCfg<D, L>;
@@ -262,11 +301,15 @@ __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
             tournament_pair(J::H, s, wave, ha, hb);
             load(a, ha * G + i);
             load(c, hb * G + i);
+            // squared norms once per super-round; they follow the rotations in closed form, and
+            // that of a B column travels with the column
+            float al = team_sum<T>(norm2_ch<CH>(a)), be = team_sum<T>(norm2_ch<CH>(c));
 #pragma unroll
             for (int j = 0; j < G; ++j) {
-                rotate_pair<T, CH>(a, c, dead2, offmax);
+                rotate_pair_with_norms<T, CH>(a, c, al, be, dead2, offmax);
                 if (j + 1 < G) {
                     // team i takes over the B column of team i + 1
+                    be = __shfl(be, (lane + T) & 63);
 #pragma unroll
                     for (int k = 0; k < CH; ++k) {
                         c[k].x = __shfl(c[k].x, (lane + T) & 63);
