@@ -42,12 +42,13 @@ constexpr int kEigWaves = kEigThreads / 64;
 constexpr float kDeadRel = 1.0e-5f;
 // Rotations are skipped below kSkipCos.  The Jacobi phase converges quadratically: a sweep whose
 // largest |cos| was c leaves about c^2 behind (L * c^2 at worst), so the phase ends after the
-// first sweep that met no |cos| above kSweepDone = 1e-3, with a few 1e-6 left; the residual
-// check of the following power step is what accepts the result.  (2e-4 costs one more sweep
-// in a third of the cases; 3e-3 leaves V^T V up to 4e-5 off the identity at 72 columns; 3e-2
-// makes the check fail and the iteration longer.)
+// first sweep that met no |cos| above kSweepDone = 5e-4, with a few 1e-6 left; the residual
+// check of the following power step is what accepts the result.  (1e-3 leaves V^T V up to 1.3e-5
+// off the identity at 72 columns and 3e-3 up to 4e-5; 3e-2 makes the check fail and the iteration
+// longer.  In a batch some user nearly always needs the sweep that a looser limit would save
+// the others, so the launch is no shorter with 1e-3.)
 constexpr float kSkipCos = 1.0e-7f;
-constexpr float kSweepDone = 1.0e-3f;
+constexpr float kSweepDone = 5.0e-4f;
 
 __host__ __device__ constexpr int pow2floor_c(int x) {
     int p = 1;
@@ -94,8 +95,9 @@ __device__ __forceinline__ float team_sum(float v) {
 // on consecutive addresses.  Q and Z are stored column by column (column j at j*LD).
 // Gb has row stride GS: the copy of G in LDS (row stride D + 16, which puts the two slot
 // groups of a half wave on disjoint banks) or, when G does not fit there, G itself.
-template <int D, int LP, int GS>
-__device__ __forceinline__ void gemm_gq(const float* Gb, const float* Qc, float* Zc) {
+// With a shift t the result is (G - t I) Q: the accumulators start from -t Q.
+template <int D, int LP, int GS, bool SHIFTED = false>
+__device__ __forceinline__ void gemm_gq(const float* Gb, const float* Qc, float* Zc, float shift = 0.f) {
     constexpr int LD = D + 4;
     constexpr int NRB = D / 16, NCB = LP / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -107,7 +109,12 @@ __device__ __forceinline__ void gemm_gq(const float* Gb, const float* Qc, float*
         const float* qb = Qc + i16 * LD + g;
         v4f acc[NCB];
 #pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) acc[cb] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int cb = 0; cb < NCB; ++cb) {
+            if constexpr (SHIFTED)
+                acc[cb] = -shift * *reinterpret_cast<const v4f*>(&Qc[(16 * cb + i16) * LD + 16 * ib + 4 * g]);
+            else
+                acc[cb] = v4f{0.f, 0.f, 0.f, 0.f};
+        }
 #pragma unroll 8
         for (int k0 = 0; k0 < D; k0 += 4) {
             const float a = ga[k0 * GS];
@@ -153,6 +160,12 @@ struct EigCfg {
 #ifndef SOLAR_JAC_T
 #define SOLAR_JAC_T 16
 #endif
+#ifndef SOLAR_EIG_EXTRA_CAP
+#define SOLAR_EIG_EXTRA_CAP 4
+#endif
+#ifndef SOLAR_JAC_NB
+#define SOLAR_JAC_NB(T) ((T) == 16)
+#endif
 // the widest team (at most SOLAR_JAC_T lanes, a float4 per lane at least) whose waves fit the workgroup
 __host__ __device__ constexpr int jacobi_team_lanes(int d, int l) {
     for (int t = SOLAR_JAC_T; t > 8; t /= 2) {
@@ -176,37 +189,65 @@ struct JacobiCfg {
     static_assert(D % (4 * T) == 0 && CH >= 1, "whole float4 per lane");
 };
 
-// the rotation of one column pair held by a team of T lanes as CH float4 per lane and column;
-// columns that have collapsed to rounding noise are left alone (dropped later)
-template <int T, int CH>
-__device__ __forceinline__ void rotate_pair(v4f (&a)[CH], v4f (&c)[CH], float dead2, float& offmax) {
-    float al = 0.f, be = 0.f, ga = 0.f;
+// The rotation that makes the columns a, c of a pair orthogonal, from their squared norms al, be
+// and inner product ga; the norms follow in closed form (al' = al - t ga, be' = be + t ga with
+// t the tangent).  With d = be - al and g = ga, both divided by |a||c| so that squares cannot
+// overflow, the rotation has cos^2 = x = 1/2 + |d| / (2 sqrt(d^2 + 4 g^2)) and
+// sin = sign(d) g / (sqrt(d^2 + 4 g^2) cos): two dependent reciprocal square roots, where the
+// route over zeta = d / 2g and the tangent takes four dependent transcendental steps.  Columns
+// that have collapsed to rounding noise are left alone (dropped later), and so are pairs whose
+// cosine is below kSkipCos.  With BRANCHLESS the rotation is always applied and a pair that is
+// left alone gets the identity: no lane branches in the chain of dependent instructions, which
+// pays while a lane holds up to eight elements per column.
+template <int T, int CH, bool BRANCHLESS>
+__device__ __forceinline__ void rotate_columns(v4f (&a)[CH], v4f (&c)[CH], float& al, float& be, float ga,
+                                               float dead2, float& offmax) {
+    const float ra = __builtin_amdgcn_rsqf(al), rb = __builtin_amdgcn_rsqf(be);
+    const float gn = ga * ra * rb;   // cosine of the angle between the columns
+    const float dn = (be - al) * ra * rb;
+    const float cosv = fabsf(gn);
+    const bool live = al > dead2 && be > dead2;
+    const bool rot = live && cosv > kSkipCos;
+    const float ih = __builtin_amdgcn_rsqf(dn * dn + 4.f * gn * gn);
+    const float x = 0.5f + 0.5f * fabsf(dn) * ih;
+    const float r = __builtin_amdgcn_rsqf(x);
+    float cs = x * r;
+    float sn = (dn >= 0.f ? gn : -gn) * ih * r;
+    float tg = sn * r * ga;
+    if constexpr (BRANCHLESS) {
+        offmax = live ? fmaxf(offmax, cosv) : offmax;
+        cs = rot ? cs : 1.f;
+        sn = rot ? sn : 0.f;
+        tg = rot ? tg : 0.f;
 #pragma unroll
-    for (int k = 0; k < CH; ++k) {
-        al += a[k].x * a[k].x + a[k].y * a[k].y + a[k].z * a[k].z + a[k].w * a[k].w;
-        be += c[k].x * c[k].x + c[k].y * c[k].y + c[k].z * c[k].z + c[k].w * c[k].w;
-        ga += a[k].x * c[k].x + a[k].y * c[k].y + a[k].z * c[k].z + a[k].w * c[k].w;
-    }
-    al = team_sum<T>(al);
-    be = team_sum<T>(be);
-    ga = team_sum<T>(ga);
-    if (al > dead2 && be > dead2) {
-        const float cosv = fabsf(ga) * __builtin_amdgcn_rsqf(al) * __builtin_amdgcn_rsqf(be);
-        offmax = fmaxf(offmax, cosv);
-        if (cosv > kSkipCos) {
-            const float zeta = 0.5f * (be - al) * __builtin_amdgcn_rcpf(ga);
-            const float t = copysignf(1.f, zeta) *
-                            __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
-            const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
-            const float sn = cs * t;
+        for (int k = 0; k < CH; ++k) {
+            const v4f x4 = a[k], y4 = c[k];
+            a[k] = cs * x4 - sn * y4;
+            c[k] = sn * x4 + cs * y4;
+        }
+        al -= tg;
+        be += tg;
+    } else {
+        if (live) offmax = fmaxf(offmax, cosv);
+        if (rot) {
 #pragma unroll
             for (int k = 0; k < CH; ++k) {
-                const v4f x = a[k], y = c[k];
-                a[k] = cs * x - sn * y;
-                c[k] = sn * x + cs * y;
+                const v4f x4 = a[k], y4 = c[k];
+                a[k] = cs * x4 - sn * y4;
+                c[k] = sn * x4 + cs * y4;
             }
+            al -= tg;
+            be += tg;
         }
     }
+}
+
+template <int CH>
+__device__ __forceinline__ float dot_ch(const v4f (&a)[CH], const v4f (&c)[CH]) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < CH; ++k) s += a[k].x * c[k].x + a[k].y * c[k].y + a[k].z * c[k].z + a[k].w * c[k].w;
+    return s;
 }
 
 // pair number k of round rho of a round-robin tournament of n players (n even): player n - 1
@@ -219,49 +260,11 @@ __device__ __forceinline__ void tournament_pair(int n, int rho, int k, int& p, i
     if (k == 0) p = n - 1;
 }
 
-// The same rotation when the squared norms of the two columns are known: only the inner product
-// is formed, and the norms follow the rotation in closed form (alpha' = alpha - t gamma,
-// beta' = beta + t gamma for the rotation that makes the pair orthogonal).
-template <int T, int CH>
-__device__ __forceinline__ void rotate_pair_with_norms(v4f (&a)[CH], v4f (&c)[CH], float& al, float& be,
-                                                       float dead2, float& offmax) {
-    float ga = 0.f;
-#pragma unroll
-    for (int k = 0; k < CH; ++k) ga += a[k].x * c[k].x + a[k].y * c[k].y + a[k].z * c[k].z + a[k].w * c[k].w;
-    ga = team_sum<T>(ga);
-    if (al > dead2 && be > dead2) {
-        const float cosv = fabsf(ga) * __builtin_amdgcn_rsqf(al) * __builtin_amdgcn_rsqf(be);
-        offmax = fmaxf(offmax, cosv);
-        if (cosv > kSkipCos) {
-            const float zeta = 0.5f * (be - al) * __builtin_amdgcn_rcpf(ga);
-            const float t = copysignf(1.f, zeta) *
-                            __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
-            const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
-            const float sn = cs * t;
-#pragma unroll
-            for (int k = 0; k < CH; ++k) {
-                const v4f x = a[k], y = c[k];
-                a[k] = cs * x - sn * y;
-                c[k] = sn * x + cs * y;
-            }
-            al -= t * ga;
-            be += t * ga;
-        }
-    }
-}
-
-template <int CH>
-__device__ __forceinline__ float norm2_ch(const v4f (&a)[CH]) {
-    float s = 0.f;
-#pragma unroll
-    for (int k = 0; k < CH; ++k) s += a[k].x * a[k].x + a[k].y * a[k].y + a[k].z * a[k].z + a[k].w * a[k].w;
-    return s;
-}
-
 template <int D, int L>
 __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
     using J = JacobiCfg<D, L>;
     constexpr int T = J::T, G = J::G, CH = J::CH, LD = EigCfg<D, L>::LD;
+    constexpr bool NB = SOLAR_JAC_NB(T);   // measured: teams of 16 lanes gain from it, teams of 8 lose
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int u = tid % T;
     float offmax = 0.f;
@@ -285,7 +288,8 @@ __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
                 tournament_pair(G, rho, k, p, q);
                 load(a, hg * G + p);
                 load(c, hg * G + q);
-                rotate_pair<T, CH>(a, c, dead2, offmax);
+                float al = team_sum<T>(dot_ch<CH>(a, a)), be = team_sum<T>(dot_ch<CH>(c, c));
+                rotate_columns<T, CH, NB>(a, c, al, be, team_sum<T>(dot_ch<CH>(a, c)), dead2, offmax);
                 store(a, hg * G + p);
                 store(c, hg * G + q);
             }
@@ -303,10 +307,10 @@ __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
             load(c, hb * G + i);
             // squared norms once per super-round; they follow the rotations in closed form, and
             // that of a B column travels with the column
-            float al = team_sum<T>(norm2_ch<CH>(a)), be = team_sum<T>(norm2_ch<CH>(c));
+            float al = team_sum<T>(dot_ch<CH>(a, a)), be = team_sum<T>(dot_ch<CH>(c, c));
 #pragma unroll
             for (int j = 0; j < G; ++j) {
-                rotate_pair_with_norms<T, CH>(a, c, al, be, dead2, offmax);
+                rotate_columns<T, CH, NB>(a, c, al, be, team_sum<T>(dot_ch<CH>(a, c)), dead2, offmax);
                 if (j + 1 < G) {
                     // team i takes over the B column of team i + 1
                     be = __shfl(be, (lane + T) & 63);
@@ -529,8 +533,18 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
     bool have_ritz = false;
     int cheap_left = prm.mgs_steps;
     int cycle = 0;
+    // the cheap steps that the convergence rate adds are filtered: step j of k applies G - t_j I
+    // with t_j the roots of the Chebyshev polynomial of degree k on [0, cheb_b]
+    float cheb_b = 0.f;
+    int cheb_k = 0, cheb_j = 0;
     for (;; ++it) {
-        gemm_gq<D, LP, C::GS>(Gop, Qc, Zc);
+        if (cheb_j < cheb_k) {
+            const float shift = 0.5f * cheb_b * (1.f + __cosf((2 * cheb_j + 1) * 1.57079632679f / cheb_k));
+            ++cheb_j;
+            gemm_gq<D, LP, C::GS, true>(Gop, Qc, Zc, shift);
+        } else {
+            gemm_gq<D, LP, C::GS>(Gop, Qc, Zc);
+        }
         __syncthreads();
         // column norms of Z (for the dead-column threshold), Rayleigh quotients and residuals
         if (col < L) {
@@ -584,7 +598,15 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
                 // factor over the r-th largest estimates lambda_(L+1) / lambda_r.  A slowly decaying
                 // spectrum (ratio above 0.3) would fail the check after the usual two steps and pay
                 // a whole Jacobi phase for it, so cheap steps are added up front instead (each costs
-                // a sixth to a tenth of that phase).  (Ending the cheap steps after one when the
+                // a sixth to a tenth of that phase), and these k steps apply G - t_j I with the t_j
+                // at the roots of the Chebyshev polynomial of degree k on [0, lambda_L]: together
+                // they are the polynomial of degree k that is smallest on the unwanted part of the
+                // spectrum relative to its value at lambda_r (at a ratio of 0.6, 1/44 after three
+                // steps where three plain power steps give 1/4.6); the Gram-Schmidt pass between two
+                // steps only changes the basis of the block, not its span.  Four filtered steps
+                // leave the residuals of the first check ten times below the tolerance where five
+                // plain ones left some users just above it, who then paid a second Jacobi phase.
+                // (Ending the cheap steps after one when the
                 // ratio is ~ 0, as for inputs of rank r, was tried: one user in eight then failed
                 // the check by a small margin and took seven steps.)
                 if (tid < L) {
@@ -603,8 +625,15 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
                 const float rho = vr > 0.f ? sqrtf(fmaxf(vmin, 0.f) / vr) : 0.f;
                 if (rho > 0.3f && rho < 1.f) {
                     const int want = (int)ceilf(-11.5f / __logf(rho)) - 3;   // ln(1e-5) = -11.5
-                    cheap_left = want < 0 ? 0 : (want > 5 ? 5 : want);
+                    cheap_left = want < 0 ? 0 : (want > SOLAR_EIG_EXTRA_CAP ? SOLAR_EIG_EXTRA_CAP : want);
                     cycle = -1;   // the rate is not looked at again
+#ifndef SOLAR_EIG_NO_CHEB
+                    // the interval that the filter damps ends at the estimate of lambda_L and in any
+                    // case well below that of lambda_r (a root next to a wanted eigenvalue would
+                    // remove that direction from the block)
+                    cheb_b = fminf(sqrtf(fmaxf(vmin, 0.f)), 0.85f * sqrtf(vr));
+                    cheb_k = cheap_left;
+#endif
                 }
             }
             continue;
