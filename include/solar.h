@@ -168,6 +168,14 @@ solar_status solar_svd_factorize_static(const void* X, const int32_t* lengths, i
  *   Q        in  [B,M,d] of type t
  *   S, V, P  in  as written by solar_svd_factorize (P may be NULL for modes 1, 2)
  *   O        out [B,M,d]
+ *
+ * Mode 0 on bf16 inputs multiplies 16-bit softmax weights on the matrix unit (2e-2 contract).
+ * A weight more than 25 log2 units below the softmax reference rounds to zero; the reference
+ * sits at most 4 log2 units above the largest score up to N = 16384, 2 up to 65536 and 0 up to
+ * 262144 (beyond that, and whenever a score would leave the 16-bit range, the reference follows
+ * the running maximum), so a flat tail of N rows loses at most N * 2^-21 ... N * 2^-25 of the
+ * softmax mass, under one percent at every N up to 262144 and 1.6 % at 524288.  Longer sequences
+ * (and float inputs, S == NULL, r not a multiple of 4) are evaluated in float arithmetic.
  */
 solar_status solar_svd_attention(const void* Q, const float* S, const float* V, const float* P,
                                  const int32_t* lengths, int B, int N, int d, int r, int M,
@@ -184,8 +192,8 @@ solar_status solar_svd_attention(const void* Q, const float* S, const float* V, 
  * they are used for many.
  *   Q  in [B,M,d] bf16     X  in [B,N,d] bf16     S, V  in  as written by solar_svd_factorize
  *   O  out [B,M,d] float
- * Supported: t = SOLAR_BF16, d in {64, 128, 256}, r a multiple of 4, r <= 64 (r <= 32 when d = 256);
- * anything else returns SOLAR_ERR_UNSUPPORTED.  No workspace is used.
+ * Supported: t = SOLAR_BF16, d in {64, 128, 256}, r a multiple of 4, r <= 64 (r <= 32 when d = 256),
+ * N <= 524288; anything else returns SOLAR_ERR_UNSUPPORTED.  No workspace is used.
  */
 solar_status solar_svd_attention_from_x(const void* Q, const void* X, const float* S, const float* V,
                                         const int32_t* lengths, int B, int N, int d, int r, int M,

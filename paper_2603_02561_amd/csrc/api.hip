@@ -78,6 +78,11 @@ EigParams eig_params() {
 }
 
 // a byte offset into one user's rows must fit the 32 bits the attention kernels keep it in
+// longest sequence for the attention kernel with 16-bit softmax weights: a weight below 2^-25 of the
+// reference rounds to zero, and in the guarded pass the largest weight is at least 1, so N rows of
+// such a tail are at most N * 2^-25 of the softmax mass (1.6 % at this length)
+constexpr int kX32MaxN = 524288;
+
 bool rows_fit_32bit(int N, size_t row_bytes) { return (size_t)N * row_bytes < ((size_t)1 << 32); }
 
 solar_status factorize_check(const void* X, int B, int N, int d, int r, solar_dtype t, const float* S,
@@ -367,8 +372,11 @@ solar_status solar_svd_attention(const void* Q, const float* S, const float* V, 
         case SOLAR_ATTN_SEQ_SOFTMAX:
             if (!P) return SOLAR_ERR_INVALID_ARG;
             // bf16 inputs with the factors' S at hand and r a multiple of 4 take the fp16
-            // matrix-unit kernel (2e-2 contract); everything else keeps float arithmetic
-            if (bf16 && S && attention_seq_x32_supported(d, r) && rows_fit_32bit(N, 4u * (size_t)r))
+            // matrix-unit kernel (2e-2 contract); everything else keeps float arithmetic, and so
+            // do sequences beyond kX32MaxN rows, where 16-bit weights could drop a flat tail
+            // that holds more than a percent of the softmax mass
+            if (bf16 && S && attention_seq_x32_supported(d, r) && rows_fit_32bit(N, 4u * (size_t)r) &&
+                N <= kX32MaxN)
                 e = launch_attention_seq_x32(Q, S, V, P, lengths, B, N, d, r, M, scale, O, st);
             else
                 e = launch_attention_seq(Q, V, P, lengths, B, N, d, r, M, scale, bf16, O, st);
@@ -394,7 +402,7 @@ solar_status solar_svd_attention_from_x(const void* Q, const void* X, const floa
     if (t != SOLAR_F32 && t != SOLAR_BF16) return SOLAR_ERR_INVALID_ARG;
     if (r > d || r > N) return SOLAR_ERR_INVALID_ARG;
     if (t != SOLAR_BF16 || !attention_seq_x32_from_x_supported(d, r)) return SOLAR_ERR_UNSUPPORTED;
-    if (!rows_fit_32bit(N, 2u * (size_t)d)) return SOLAR_ERR_UNSUPPORTED;
+    if (!rows_fit_32bit(N, 2u * (size_t)d) || N > kX32MaxN) return SOLAR_ERR_UNSUPPORTED;
     hipError_t e = launch_attention_seq_x32_from_x(Q, S, V, X, lengths, B, N, d, r, M, scale, O, (hipStream_t)stream);
     return e == hipSuccess ? SOLAR_OK : SOLAR_ERR_HIP;
 }

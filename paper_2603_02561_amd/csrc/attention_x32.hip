@@ -65,9 +65,14 @@ constexpr float kLog2e = 1.4426950408889634f;
 #define SOLAR_X32_KSHIFT 8.f
 #endif
 constexpr float kShift = SOLAR_X32_KSHIFT;
-// optimistic pass: the reference stays kHead log2 units above the largest score of the first
-// block, so weights stay inside the fp16 range while no score lies more than 16 + kHead above it
-constexpr float kHead = 4.f;
+// optimistic pass: the reference stays `head` log2 units above the largest score of the first
+// block, so weights stay inside the fp16 range while no score lies more than 16 + head above it.
+// A weight below 2^-25 rounds to zero, so against a peak weight of 2^-head a flat tail of N rows
+// can lose N * 2^(head - 25) of the softmax mass at worst; the host lowers the head room with N
+// so that this stays below 2^-7: 4 up to N = 16384, 2 up to 65536, 0 up to 262144, and the
+// guarded pass alone beyond that (its peak weight is at least 1).
+inline float optimistic_head_room(int N) { return N <= 16384 ? 4.f : (N <= 65536 ? 2.f : 0.f); }
+constexpr int kOptimisticMaxN = 262144;
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v2h __attribute__((ext_vector_type(2)));
@@ -119,7 +124,7 @@ template <int D, int RP, bool FUSED>
 __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
     const void* __restrict__ Qv, const float* __restrict__ S, const float* __restrict__ V,
     const void* __restrict__ Pin, const int32_t* __restrict__ lengths, int B, int N, int r, int M,
-    float scale, int guarded_only, int longest_first, float* __restrict__ O) {
+    float scale, int guarded_only, float head, int longest_first, float* __restrict__ O) {
     static_assert(RP == 32 || RP == 64, "one or two 32-rank halves");
     static_assert(RP == 32 || D <= 128, "the bf16 images of V for 64 ranks of d = 256 do not fit LDS");
     constexpr int LDR = RP + 8, kBuf = kNT * LDR;
@@ -576,9 +581,9 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 
     // ---- the sequence loop ---------------------------------------------------------------------
     // Two versions of one pass over the sequence.  The optimistic one keeps the reference where
-    // the first block put it (kHead above that block's largest score) and spends nothing on the
+    // the first block put it (`head` above that block's largest score) and spends nothing on the
     // scores before they are exponentiated.  It is exact as long as every weight fits fp16,
-    // i.e. no score lies 16 + kHead log2 units above the first block's maximum; a weight
+    // i.e. no score lies 16 + head log2 units above the first block's maximum; a weight
     // beyond that rounds to infinity, which the row sum keeps.  If that happened to any query
     // of the workgroup, the guarded version (block maxima before every exponentiation, lazily
     // moving reference) runs the sequence again from the start.
@@ -607,7 +612,7 @@ __global__ __launch_bounds__(kThreads) void attention_seq_x32_kernel(
 #pragma unroll
         for (int t = 0; t < 16; ++t) s[1][t] = 0.f;
         mask_block(0, 0);
-        move_reference(0, true, guarded ? 0.f : kHead);
+        move_reference(0, true, guarded ? 0.f : head);
     }
     // byte-free rotation of the three tile buffers: element offsets of the tile being
     // multiplied, the next one and the one being converted
@@ -724,7 +729,8 @@ template <int D, int RP, bool FUSED>
 hipError_t launch_d(const void* Q, const float* S, const float* V, const void* P, const int32_t* lengths,
                     int B, int N, int r, int M, float scale, float* O, hipStream_t stream) {
     // debug switch (solar_debug_option): skip the optimistic pass
-    const int guarded_only = debug_force_guarded_pass() ? 1 : 0;
+    const int guarded_only = (debug_force_guarded_pass() || N > kOptimisticMaxN) ? 1 : 0;
+    const float head = optimistic_head_room(N);
     constexpr int kBuf = kNT * (RP + 8);
     const size_t lds = sizeof(uint16_t) * (3 * (size_t)kBuf + 2 * RP * (size_t)(D + 8) + 2 * D * (size_t)(RP + 8)) + 16;
     dim3 grid(ceil_div(M, kWaves * kQW) * 8 * ceil_div(B, 8)), block(kThreads);
@@ -735,7 +741,7 @@ hipError_t launch_d(const void* Q, const float* S, const float* V, const void* P
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, block, lds, stream, Q, S, V, P, lengths, B, N, r, M, scale, guarded_only,
-                       longest_first, O);
+                       head, longest_first, O);
     return hipGetLastError();
 }
 

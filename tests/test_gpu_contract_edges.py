@@ -45,7 +45,8 @@ def rel_err(got, want):
     return max(np.abs(got[b] - want[b]).max() / np.abs(want[b]).max() for b in range(want.shape[0]))
 
 
-@pytest.mark.parametrize("N,r,M", [(16384, 32, 96), (12000, 64, 80), (10240, 32, 64)])
+@pytest.mark.parametrize("N,r,M", [(16384, 32, 96), (12000, 64, 80), (10240, 32, 64), (40000, 32, 48),
+                                   (100000, 32, 40)])
 def test_scores_falling_from_the_first_block(lib, oracle, N, r, M):
     import torch
     d, B = 128, 2
