@@ -29,13 +29,7 @@ namespace solar {
 
 namespace {
 
-#ifndef SOLAR_EIG_THREADS
-#define SOLAR_EIG_THREADS 512
-#endif
-#ifndef SOLAR_EIG_TMAX
-#define SOLAR_EIG_TMAX 16
-#endif
-constexpr int kEigThreads = SOLAR_EIG_THREADS;
+constexpr int kEigThreads = 512;
 constexpr int kEigWaves = kEigThreads / 64;
 // A column of the iterate whose norm falls below this fraction of the largest column norm
 // is rounding noise of the float Gram matrix (about sqrt(d) * 2^-24 relative) and is dropped.
@@ -131,11 +125,7 @@ template <int D, int L>
 struct EigCfg {
     static constexpr int LP = 16 * ((L + 15) / 16);
     static constexpr int LD = D + 4;
-    static constexpr int NPAIR = L / 2;
-    // lanes per column pair in a Jacobi round, lanes per column elsewhere
-    // (at most 16, so that a team's sums are pure DPP exchanges)
-    static constexpr int TJ = min_c(min_c(SOLAR_EIG_TMAX, D / 4), pow2floor_c(kEigThreads / NPAIR));
-    static constexpr int CH = D / (4 * TJ);
+    // lanes per column outside the Jacobi rounds
     static constexpr int TC = min_c(min_c(64, D), pow2floor_c(kEigThreads / L));
     // G is staged in LDS when it fits beside the two iterate blocks
     static constexpr bool GLDS = D <= 128;
@@ -157,18 +147,11 @@ struct EigCfg {
 // workgroup barrier only between them, and the pairs inside a half-group are taken first, G - 1
 // rounds through LDS.  The number of rotations per sweep is that of any cyclic ordering; the
 // barriers drop from L - 1 to (H - 1) + (G - 1).
-#ifndef SOLAR_JAC_T
-#define SOLAR_JAC_T 16
-#endif
-#ifndef SOLAR_EIG_EXTRA_CAP
-#define SOLAR_EIG_EXTRA_CAP 4
-#endif
-#ifndef SOLAR_JAC_NB
-#define SOLAR_JAC_NB(T) ((T) == 16)
-#endif
-// the widest team (at most SOLAR_JAC_T lanes, a float4 per lane at least) whose waves fit the workgroup
+// most power steps that a slow convergence rate may add before the first Jacobi phase
+constexpr int kExtraStepsCap = 4;
+// the widest team (at most 16 lanes, a float4 per lane at least) whose waves fit the workgroup
 __host__ __device__ constexpr int jacobi_team_lanes(int d, int l) {
-    for (int t = SOLAR_JAC_T; t > 8; t /= 2) {
+    for (int t = 16; t > 8; t /= 2) {
         const int g = 64 / t;
         if (4 * t <= d && (l + 2 * g - 1) / (2 * g) <= kEigWaves) return t;
     }
@@ -264,7 +247,7 @@ template <int D, int L>
 __device__ __forceinline__ float jacobi_sweep(float* Zc, float dead2) {
     using J = JacobiCfg<D, L>;
     constexpr int T = J::T, G = J::G, CH = J::CH, LD = EigCfg<D, L>::LD;
-    constexpr bool NB = SOLAR_JAC_NB(T);   // measured: teams of 16 lanes gain from it, teams of 8 lose
+    constexpr bool NB = T == 16;   // measured: teams of 16 lanes gain from it, teams of 8 lose
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int u = tid % T;
     float offmax = 0.f;
@@ -625,15 +608,13 @@ __global__ __launch_bounds__(kEigThreads) void eig_topr_kernel(
                 const float rho = vr > 0.f ? sqrtf(fmaxf(vmin, 0.f) / vr) : 0.f;
                 if (rho > 0.3f && rho < 1.f) {
                     const int want = (int)ceilf(-11.5f / __logf(rho)) - 3;   // ln(1e-5) = -11.5
-                    cheap_left = want < 0 ? 0 : (want > SOLAR_EIG_EXTRA_CAP ? SOLAR_EIG_EXTRA_CAP : want);
+                    cheap_left = want < 0 ? 0 : (want > kExtraStepsCap ? kExtraStepsCap : want);
                     cycle = -1;   // the rate is not looked at again
-#ifndef SOLAR_EIG_NO_CHEB
                     // the interval that the filter damps ends at the estimate of lambda_L and in any
                     // case well below that of lambda_r (a root next to a wanted eigenvalue would
                     // remove that direction from the block)
                     cheb_b = fminf(sqrtf(fmaxf(vmin, 0.f)), 0.85f * sqrtf(vr));
                     cheb_k = cheap_left;
-#endif
                 }
             }
             continue;
