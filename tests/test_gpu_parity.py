@@ -347,3 +347,28 @@ def test_iteration_cap_is_reported_per_user(lib):
     db.factorize()
     torch.cuda.synchronize()
     assert np.all(db.info.cpu().numpy() == 0)
+
+
+@pytest.mark.parametrize("r,with_s", [(16, False), (6, True), (6, False)])
+def test_bf16_inputs_in_float_arithmetic(lib, oracle, r, with_s):
+    """Mode 0 on bf16 inputs outside the 16-bit matrix-unit kernel's domain -- no S at hand, or a
+    rank that is not a multiple of four (very long sequences take the same route): the scores and
+    weights are then evaluated in float, so the float gate of 1e-4 applies, not the 2e-2 of the
+    16-bit weights."""
+    import torch
+    w = synth.make_workload("t", 3, 700, 128, r, 90, synth.BF16, "gauss_lowrank", var_len=(300, 700), seed=4400 + r)
+    print(f"[case] bf16 inputs, float attention kernel, r={r} S {'given' if with_s else 'absent'}", flush=True)
+    db = lib.DeviceBatch(w.X, w.Q, w.lengths, w.r, True)
+    db.factorize()
+    torch.cuda.synchronize()
+    assert np.all(db.info.cpu().numpy() == 0)
+    f = oracle.svd_factorize(w.X, w.r, w.lengths)
+    for scale in (1.0, w.sharp_scale):
+        lib.solar_svd_attention(db.Q, db.S if with_s else None, db.V, db.P, db.lengths, w.N, scale, 0, db.O,
+                                db.workspace)
+        torch.cuda.synchronize()
+        want = oracle.svd_attention(w.Q, w.X, f["S"], f["V"], scale, 0, w.lengths)
+        got = db.O.cpu().numpy().astype(np.float64)
+        err = max(np.abs(got[b] - want[b]).max() / np.abs(want[b]).max() for b in range(w.B))
+        print(f"  scale {scale:.3g}: {err:.3e}", flush=True)
+        assert err < 1e-4
